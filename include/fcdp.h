@@ -1,0 +1,269 @@
+/*
+ * fcdp.h -- C ABI of the FCDP per-layer hot path for one AMD MI355X (gfx950).
+ *
+ * What the path is (paper Sec. 2.1, Sec. 4.3-4.5, Alg. 1, Sec. 6.1-6.3): under
+ * fully sharded data parallelism each of the G ranks keeps a 1/G shard of a
+ * layer's flat parameter buffer; the full per-tensor parameters are rebuilt
+ * before the forward and again before the backward computation; FCDP keeps
+ * the forward copy in pinned host memory and rebuilds the backward copy from
+ * there; gradients are summed over ranks and each rank keeps the shard that
+ * matches its parameter shard; under PEFT only trainable parameters travel.
+ * This library is the part of that path that runs on one GPU.  Peers' shards
+ * and partial gradients are ordinary device buffers handed in by the caller.
+ *
+ * Flat layout (the paper inherits it from its substrate and does not print
+ * it; this is the reading used here): the T tensors of a layer are laid end
+ * to end in the order given to fcdp_layout_build, tightly packed; the total
+ * N is padded with zero elements at the tail to N_pad, a multiple of
+ * G*pad_quantum; shard r is the flat range [r*S, (r+1)*S), S = N_pad/G.
+ *
+ * Conventions for every call below
+ *   - "dev ptr" is a device address valid on the current HIP device; "host
+ *     ptr" is an ordinary host address.  Arrays of pointers (shard_ptrs,
+ *     tensor_ptrs, partial_ptrs) are HOST arrays whose entries are dev ptrs;
+ *     they are read during the call and may be freed right after it returns.
+ *   - Ownership: the caller owns every data buffer.  The library owns only
+ *     fcdp_layout / fcdp_cache_state objects and memory returned by
+ *     fcdp_host_cache_alloc (freed with fcdp_host_cache_free).
+ *   - Streams are hipStream_t values passed as void* (NULL = the default
+ *     stream).  Data calls only enqueue work; they never synchronise the
+ *     device, except the first data call on a layout, which uploads the
+ *     layout's tables (call fcdp_layout_prepare beforehand to avoid that).
+ *   - Every data base pointer must be 16-byte aligned (FCDP_EALIGN if not).
+ *     Offsets inside a buffer may be any element index.
+ *   - Errors: a status code is returned, nothing is thrown and nothing
+ *     aborts.  All argument checks precede the first enqueue, so a call that
+ *     fails an argument check has no side effect.  fcdp_last_error() gives a
+ *     thread-local text for the last failing call on the calling thread.
+ *   - Zero-element tensors, N = 0 and N_t = 0 are legal no-ops.
+ */
+#ifndef FCDP_H
+#define FCDP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fcdp_layout fcdp_layout;           /* immutable after build */
+typedef struct fcdp_cache_state fcdp_cache_state; /* dirty flags, host only */
+typedef void *fcdp_stream;                        /* a hipStream_t */
+
+typedef enum {
+    FCDP_OK = 0,
+    FCDP_EINVAL = 1,     /* NULL pointer, bad count, bad enum, aliasing */
+    FCDP_ESIZE = 2,      /* a size beyond a documented limit */
+    FCDP_EALIGN = 3,     /* a base pointer that is not 16-byte aligned */
+    FCDP_ENOTPINNED = 4, /* host_cache is not mapped pinned host memory */
+    FCDP_ESTATE = 5,     /* cache-state call out of order */
+    FCDP_ENOMEM = 6,     /* allocation failed */
+    FCDP_EHIP = 7        /* a HIP runtime call failed; see fcdp_last_error */
+} fcdp_status;
+
+typedef enum { FCDP_BF16 = 0, FCDP_F32 = 1 } fcdp_dtype;
+
+typedef enum {
+    FCDP_SRC_DEVICE_SHARDS = 0, /* cache miss: scatter the G gathered shards */
+    FCDP_SRC_HOST_DMA = 1,      /* cache hit: DMA host cache -> staging, scatter */
+    FCDP_SRC_HOST_ZEROCOPY = 2  /* cache hit: kernel reads the mapped host cache */
+} fcdp_source;
+
+#define FCDP_MAX_G 64 /* most shards / gradient partials per call */
+
+/* ------------------------------------------------------------ offset table
+ * Builds the layout of one layer (Sec. 2.1 "ZeRO-3 shards ... across all
+ * GPUs"; Sec. 6.1 "each GPU stores a shard of size W/G").
+ *   numel[t]      elements of tensor t (>= 0), t in [0, n_tensors)
+ *   trainable[t]  1 = trainable (W_t), 0 = frozen (W_f); NULL = all trainable
+ *                 (Sec. 4.5: parameters are classified once, at initialisation)
+ *   G             number of ranks = shards, 1..FCDP_MAX_G
+ *   elem_size     bytes per element, 2 (bf16) or 4
+ *   pad_quantum   q: N_pad is a multiple of G*q (64 in all shipped configs)
+ * Host-only; needs no GPU.  *out is owned by the library until
+ * fcdp_layout_destroy.  Errors: FCDP_EINVAL, FCDP_ESIZE (G > FCDP_MAX_G or
+ * a flat size that would overflow), FCDP_ENOMEM.
+ */
+fcdp_status fcdp_layout_build(const int64_t *numel, const uint8_t *trainable,
+                              int32_t n_tensors, int32_t G, int32_t elem_size,
+                              int32_t pad_quantum, fcdp_layout **out);
+void fcdp_layout_destroy(fcdp_layout *layout);
+
+int32_t fcdp_layout_n_tensors(const fcdp_layout *layout);
+int32_t fcdp_layout_G(const fcdp_layout *layout);
+int32_t fcdp_layout_elem_size(const fcdp_layout *layout);
+int64_t fcdp_layout_numel(const fcdp_layout *layout);           /* N      */
+int64_t fcdp_layout_padded_numel(const fcdp_layout *layout);    /* N_pad  */
+int64_t fcdp_layout_shard_numel(const fcdp_layout *layout);     /* S      */
+int64_t fcdp_layout_trainable_numel(const fcdp_layout *layout); /* N_t    */
+int64_t fcdp_layout_packed_numel(const fcdp_layout *layout);    /* N_t up to G*q */
+/* off[0..T]; borrowed, valid until destroy */
+const int64_t *fcdp_layout_offsets(const fcdp_layout *layout);
+/* Segment list: every non-empty (tensor x shard) overlap in (tensor, shard)
+ * order, rows of 5 int64 (t, r, dst_off, src_off, len): len elements of
+ * shard r starting at src_off form tensor t's elements from dst_off.
+ * Returns the number of rows; writes at most cap rows. */
+int64_t fcdp_layout_segments(const fcdp_layout *layout, int64_t *rows,
+                             int64_t cap);
+/* The copy plan a kernel walks, for inspection and host-side checking:
+ * which = 0 unflatten (shards -> tensors), 1 flatten (tensors -> shards),
+ * 2 pack (flat -> packed), 3 unpack (packed -> flat).  Rows of 5 int64
+ * (src_idx, src_byte_off, dst_idx, dst_byte_off, nbytes); src_idx = -1 means
+ * "write zeros".  Indices are shard or tensor numbers (0 for flat/packed).
+ * Returns the number of rows (-1 on a bad argument); writes at most cap. */
+int64_t fcdp_layout_copy_plan(const fcdp_layout *layout, int32_t which,
+                              int64_t *rows, int64_t cap);
+/* Uploads the layout's copy tables to the current device (synchronous,
+ * idempotent).  Data calls do it on first use if it was not called. */
+fcdp_status fcdp_layout_prepare(const fcdp_layout *layout);
+
+/* ---------------------------------------------------- layer materialization
+ * Rebuilds the T per-tensor parameter buffers of one layer.
+ *
+ * FCDP_SRC_DEVICE_SHARDS (forward, cache miss; Sec. 4.3 forward pass, Alg. 1
+ * dirty branch "p <- AllGather(p_inter)"): tensor_t[j] =
+ * shard_{(off_t+j) div S}[(off_t+j) mod S].  If store_cache != 0 the padded
+ * flat image concat(shard_0..shard_{G-1}) is also copied to host_cache on the
+ * `copy` stream (Alg. 1 "H[p] <- p", gpu to host), ordered after everything
+ * enqueued on `compute` before this call; the shards must stay unmodified
+ * until that copy has completed in `copy`-stream order.
+ *
+ * FCDP_SRC_HOST_DMA (backward / clean forward, cache hit; Sec. 4.3 backward
+ * pass, Alg. 1 "p_intra <- H[p]"): host_cache is copied to `staging` on the
+ * `copy` stream, then the scatter runs on `compute` after it.  The library
+ * remembers the last scatter that read each staging buffer and makes the
+ * next copy into that buffer wait for it, so alternating two staging
+ * buffers overlaps the fetch of one layer with the scatter of another.
+ *
+ * FCDP_SRC_HOST_ZEROCOPY: one kernel on `compute` reads host_cache through
+ * its device mapping and writes the tensors; ordered after everything
+ * enqueued on `copy` before this call.  host_cache must be mapped pinned
+ * host memory (fcdp_host_cache_alloc), else FCDP_ENOTPINNED.
+ *
+ *   shard_ptrs   host array of G dev ptrs, S*elem_size bytes each
+ *                (DEVICE_SHARDS only, else may be NULL)
+ *   host_cache   host ptr to N_pad*elem_size bytes of pinned memory; read
+ *                for HOST_*, written when store_cache != 0; else may be NULL
+ *   staging      dev ptr to N_pad*elem_size bytes (HOST_DMA only)
+ *   tensor_ptrs  host array of T dev ptrs, numel[t]*elem_size bytes each
+ *                (entries of zero-element tensors are ignored)
+ * Results are valid in `compute`-stream order (tensors) and `copy`-stream
+ * order (host_cache).  Padding is never read into a tensor.
+ */
+fcdp_status fcdp_materialize_layer(const fcdp_layout *layout, fcdp_source src,
+                                   const void *const *shard_ptrs,
+                                   void *host_cache, void *staging,
+                                   void *const *tensor_ptrs, int store_cache,
+                                   fcdp_stream compute, fcdp_stream copy);
+
+/* Inverse of the scatter, for initialisation and tests: writes the G shards
+ * from the T tensors and zero-fills the tail padding. */
+fcdp_status fcdp_flatten_to_shards(const fcdp_layout *layout,
+                                   const void *const *tensor_ptrs,
+                                   void *const *shard_ptrs, fcdp_stream stream);
+
+/* ------------------------------------------------------ gradient-shard sum
+ * The local half of the gradient reduce-scatter (Sec. 2.1; Sec. 6.2
+ * "Gradient reduce-scatter"; Alg. 1 "ReduceScatter(grad W_t)"): for k in
+ * [0, count)
+ *     acc = p_0[e0+k];  acc = acc + p_g[e0+k]  for g = 1..G-1, in that order
+ *     out[k] = acc                      (out == FCDP_F32)
+ *     out[k] = bf16(acc), nearest-even  (out == FCDP_BF16)
+ * in IEEE binary32 with one rounding per addition, denormals kept.  The sum,
+ * not the mean, is produced.  NaN in gives NaN out; which NaN payload is not
+ * specified.
+ *   partial_ptrs  host array of G dev ptrs to rank g's buffer base
+ *   elem_offset   e0: r*S for a whole flat gradient, 0 if the pointers
+ *                 already address the slice
+ *   in            dtype of the partials (FCDP_F32 or FCDP_BF16)
+ *   out_shard     dev ptr, count elements of dtype `out`.  It may be exactly
+ *                 partial_ptrs[g] + e0 for one g when in == out (in place);
+ *                 any other overlap with an input is FCDP_EINVAL.
+ * Errors: G outside 1..FCDP_MAX_G -> FCDP_ESIZE; count < 0 or e0 < 0 ->
+ * FCDP_EINVAL.
+ */
+fcdp_status fcdp_reduce_grad_shard(const void *const *partial_ptrs, int32_t G,
+                                   int64_t elem_offset, int64_t count,
+                                   fcdp_dtype in, fcdp_dtype out,
+                                   void *out_shard, fcdp_stream stream);
+
+/* --------------------------------------------------- PEFT pack and unpack
+ * Under PEFT only trainable parameters cross the node boundary (Sec. 4.5,
+ * Alg. 1's dirty branch and its reduce-scatter of grad W_t).
+ * Pack: the flat ranges of the trainable tensors, in tensor order, are
+ * copied end to end into `packed`; packed[N_t .. packed_numel) is set to 0.
+ * Unpack: the inverse writes; no other byte of `flat` is written (frozen
+ * parameters and the tail padding are left as they are).
+ *   flat    dev ptr, N_pad elements (unpack: may also be the device alias of
+ *           a mapped host cache, which refreshes H for W_t only)
+ *   packed  dev ptr, packed_numel elements
+ * flat and packed must not overlap.
+ */
+fcdp_status fcdp_pack_trainable(const fcdp_layout *layout, const void *flat,
+                                void *packed, fcdp_stream stream);
+fcdp_status fcdp_unpack_trainable(const fcdp_layout *layout,
+                                  const void *packed, void *flat,
+                                  fcdp_stream stream);
+
+/* ------------------------------------------------------------- host cache
+ * Pinned, device-mapped host memory for the cache H (Sec. 4.4 "Host Memory
+ * Optimization": allocated once, kept for the whole run, updated in place,
+ * taken from the NUMA node local to the GPU).  numa_node >= 0 binds the
+ * pages to that node (best effort: if the kernel refuses the policy the
+ * allocation still succeeds and fcdp_last_error() says so); -1 = no policy.
+ * *host is the host address, *dev_alias the address kernels use.
+ */
+fcdp_status fcdp_host_cache_alloc(size_t bytes, int numa_node, void **host,
+                                  void **dev_alias);
+fcdp_status fcdp_host_cache_free(void *host);
+
+/* ------------------------------------------------------------ dirty state
+ * The cache-validity flags of Alg. 1, per (layer, class) with class 0 =
+ * frozen, 1 = trainable.  All flags start dirty (nothing is cached yet).
+ * forward_source: a dirty class must be served from the gathered device
+ * shards and stored (*src = DEVICE_SHARDS, *store_cache = 1) and becomes
+ * clean; a clean class is served from the host cache (*src = host_mode,
+ * *store_cache = 0).  backward_source: always the host cache; FCDP_ESTATE if
+ * the class is still dirty (no forward has stored it).  optimizer_step marks
+ * the trainable class of every layer dirty (frozen stays clean for ever).
+ * host_mode must be FCDP_SRC_HOST_DMA or FCDP_SRC_HOST_ZEROCOPY.
+ */
+fcdp_status fcdp_cache_state_create(int32_t n_layers, fcdp_cache_state **out);
+void fcdp_cache_state_destroy(fcdp_cache_state *state);
+fcdp_status fcdp_cache_state_forward_source(fcdp_cache_state *state,
+                                            int32_t layer, int32_t klass,
+                                            fcdp_source host_mode,
+                                            fcdp_source *src,
+                                            int32_t *store_cache);
+fcdp_status fcdp_cache_state_backward_source(const fcdp_cache_state *state,
+                                             int32_t layer, int32_t klass,
+                                             fcdp_source host_mode,
+                                             fcdp_source *src);
+fcdp_status fcdp_cache_state_optimizer_step(fcdp_cache_state *state);
+/* 1 dirty, 0 clean, -1 bad argument */
+int32_t fcdp_cache_state_is_dirty(const fcdp_cache_state *state, int32_t layer,
+                                  int32_t klass);
+
+/* ------------------------------------------------------------------- misc */
+const char *fcdp_status_string(fcdp_status status);
+const char *fcdp_last_error(void);
+
+/* Launch-shape knobs for measurement sweeps (block size, bytes per work item,
+ * workgroups per compute unit, non-temporal access).  Unknown name or a value
+ * outside the documented range -> FCDP_EINVAL.  Knobs that shape the copy
+ * tables take effect for layouts built afterwards.  Not needed for normal
+ * use; the defaults are the measured best on MI355X. */
+fcdp_status fcdp_tuning_set(const char *name, int64_t value);
+int64_t fcdp_tuning_get(const char *name); /* -1 if unknown */
+
+/* A plain contiguous device copy of `bytes` bytes with the same inner loop as
+ * the scatter kernels; the known-size reference used to calibrate hardware
+ * byte counters and to state the copy speed this GPU reaches. */
+fcdp_status fcdp_probe_copy(void *dst, const void *src, size_t bytes,
+                            fcdp_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FCDP_H */

@@ -1,0 +1,15 @@
+"""FCDP per-layer hot path for one MI355X: Python binding of libfcdp.so.
+
+The binding only marshals arguments; every step of the path runs in the HIP
+library.  Importing the package does not load the library; the first call
+does, and raises if it has not been built (there is no CPU fallback).
+"""
+from .binding import (  # noqa: F401
+    BF16, F32, SRC_DEVICE_SHARDS, SRC_HOST_DMA, SRC_HOST_ZEROCOPY, MAX_G,
+    FcdpError, Layout, CacheState, HostCache,
+    fcdp_layout_build, fcdp_materialize_layer, fcdp_flatten_to_shards,
+    fcdp_reduce_grad_shard, fcdp_pack_trainable, fcdp_unpack_trainable,
+    fcdp_host_cache_alloc, fcdp_host_cache_free, fcdp_tuning_set,
+    fcdp_tuning_get, fcdp_probe_copy, fcdp_last_error, load_library,
+    library_path,
+)

@@ -1,0 +1,613 @@
+// C ABI of libfcdp: argument checks, stream/event ordering, the host cache,
+// the dirty-state flags, and the calls into the kernel launchers.
+#include <hip/hip_runtime.h>
+
+#include <sys/syscall.h>
+#include <unistd.h>
+
+#include <algorithm>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "fcdp_internal.h"
+
+using fcdp::fail;
+
+namespace {
+
+fcdp_status hip_fail(hipError_t e, const char *what)
+{
+    return fail(FCDP_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define FCDP_HIP(call, what)                                                   \
+    do {                                                                       \
+        hipError_t e_ = (call);                                                \
+        if (e_ != hipSuccess) return hip_fail(e_, what);                       \
+    } while (0)
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ----------------------------------------------------------------- events
+// A ring of timing-disabled events for "record on A, wait on B" edges, and a
+// small table that remembers, per staging buffer, the event recorded after
+// the last scatter that read it.
+struct DeviceCtx {
+    std::mutex mu;
+    std::vector<hipEvent_t> ring;
+    size_t next = 0;
+    struct StagingUse {
+        void *staging = nullptr;
+        hipEvent_t done = nullptr;
+        uint64_t stamp = 0;
+    };
+    StagingUse uses[8];
+    uint64_t clock = 0;
+};
+
+DeviceCtx g_ctx[fcdp::kMaxDevices];
+constexpr size_t kRing = 64;
+
+fcdp_status current_ctx(DeviceCtx **out)
+{
+    int dev = 0;
+    FCDP_HIP(hipGetDevice(&dev), "hipGetDevice");
+    if (dev < 0 || dev >= fcdp::kMaxDevices)
+        return fail(FCDP_ESIZE, "device ordinal beyond 15 is not supported");
+    *out = &g_ctx[dev];
+    return FCDP_OK;
+}
+
+// dst stream waits for everything enqueued so far on src stream
+fcdp_status order_after(DeviceCtx *ctx, hipStream_t src, hipStream_t dst)
+{
+    if (src == dst) return FCDP_OK;
+    hipEvent_t ev;
+    {
+        std::lock_guard<std::mutex> lk(ctx->mu);
+        if (ctx->ring.size() < kRing) {
+            hipEvent_t e;
+            FCDP_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming), "hipEventCreate");
+            ctx->ring.push_back(e);
+            ev = e;
+        } else {
+            ev = ctx->ring[ctx->next];
+            ctx->next = (ctx->next + 1) % kRing;
+        }
+    }
+    FCDP_HIP(hipEventRecord(ev, src), "hipEventRecord");
+    FCDP_HIP(hipStreamWaitEvent(dst, ev, 0), "hipStreamWaitEvent");
+    return FCDP_OK;
+}
+
+fcdp_status staging_slot(DeviceCtx *ctx, void *staging, DeviceCtx::StagingUse **out)
+{
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    DeviceCtx::StagingUse *lru = &ctx->uses[0];
+    for (auto &u : ctx->uses) {
+        if (u.staging == staging) {
+            u.stamp = ++ctx->clock;
+            *out = &u;
+            return FCDP_OK;
+        }
+        if (u.stamp < lru->stamp) lru = &u;
+    }
+    if (!lru->done)
+        FCDP_HIP(hipEventCreateWithFlags(&lru->done, hipEventDisableTiming), "hipEventCreate");
+    else if (lru->staging) {
+        // Recycling a slot: its buffer loses its tracking, so drain the old
+        // reader now (rare: more than 8 staging buffers in rotation).
+        FCDP_HIP(hipEventSynchronize(lru->done), "hipEventSynchronize");
+    }
+    lru->staging = nullptr; // "no reader recorded yet"
+    lru->stamp = ++ctx->clock;
+    *out = lru;
+    return FCDP_OK;
+}
+
+// ---------------------------------------------------------- device tables
+fcdp_status upload(const std::vector<fcdp::Piece> &v, fcdp::Piece **out)
+{
+    *out = nullptr;
+    if (v.empty()) return FCDP_OK;
+    const size_t bytes = v.size() * sizeof(fcdp::Piece);
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) return fail(FCDP_ENOMEM, std::string("hipMalloc(piece table): ") + hipGetErrorString(e));
+    e = hipMemcpy(p, v.data(), bytes, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        (void)hipFree(p);
+        return hip_fail(e, "hipMemcpy(piece table)");
+    }
+    *out = static_cast<fcdp::Piece *>(p);
+    return FCDP_OK;
+}
+
+fcdp_status tables_for_current_device(const fcdp_layout *L, const fcdp::DeviceTables **out)
+{
+    int dev = 0;
+    FCDP_HIP(hipGetDevice(&dev), "hipGetDevice");
+    std::lock_guard<std::mutex> lk(L->mu);
+    for (const auto &d : L->dev)
+        if (d.device == dev) {
+            *out = &d;
+            return FCDP_OK;
+        }
+    if (L->dev.capacity() < fcdp::kMaxDevices) L->dev.reserve(fcdp::kMaxDevices);
+    if (L->dev.size() >= fcdp::kMaxDevices)
+        return fail(FCDP_ESIZE, "layout used on more than 16 devices");
+    fcdp::DeviceTables d;
+    d.device = dev;
+    fcdp_status st;
+    if ((st = upload(L->unflatten.pieces, &d.unflatten)) != FCDP_OK) return st;
+    if ((st = upload(L->flatten.pieces, &d.flatten)) != FCDP_OK) return st;
+    if ((st = upload(L->pack.pieces, &d.pack)) != FCDP_OK) return st;
+    if ((st = upload(L->unpack.pieces, &d.unpack)) != FCDP_OK) return st;
+    L->dev.push_back(d); // reserved above: earlier pointers stay valid
+    *out = &L->dev.back();
+    return FCDP_OK;
+}
+
+// Runs one tensor-windowed piece table.
+fcdp_status run_windowed(const fcdp::PieceTable &tab, const fcdp::Piece *dev_pieces,
+                         fcdp::TensorSide side, int32_t T,
+                         const void *const *small, int32_t n_small,
+                         const void *const *tensors, bool nt, int64_t wg_per_cu,
+                         hipStream_t st, const char *what)
+{
+    const int64_t n_win = static_cast<int64_t>(tab.win_begin.size()) - 1;
+    for (int64_t w = 0; w < n_win; ++w) {
+        const int64_t b = tab.win_begin[w], e = tab.win_begin[w + 1];
+        if (e <= b) continue;
+        fcdp::CopyLaunch c;
+        c.pieces = dev_pieces + b;
+        c.n_pieces = e - b;
+        c.tensor_side = side;
+        c.tensor_base = static_cast<int32_t>(w * fcdp::kTensorWindow);
+        c.small_ptrs = small;
+        c.n_small = n_small;
+        c.tensor_ptrs = tensors + c.tensor_base;
+        c.n_tensor = std::min<int32_t>(fcdp::kTensorWindow, T - c.tensor_base);
+        c.nt = nt;
+        c.wg_per_cu = wg_per_cu;
+        hipError_t err = static_cast<hipError_t>(fcdp::launch_copy(c, st));
+        if (err != hipSuccess) return hip_fail(err, what);
+    }
+    return FCDP_OK;
+}
+
+fcdp_status check_tensor_ptrs(const fcdp_layout *L, const void *const *tensor_ptrs, const char *fn)
+{
+    if (!tensor_ptrs) return fail(FCDP_EINVAL, std::string(fn) + ": tensor_ptrs is NULL");
+    for (int32_t t = 0; t < L->T; ++t) {
+        if (L->numel[t] == 0) continue;
+        if (!tensor_ptrs[t]) return fail(FCDP_EINVAL, std::string(fn) + ": a tensor pointer is NULL");
+        if (!aligned16(tensor_ptrs[t])) return fail(FCDP_EALIGN, std::string(fn) + ": a tensor pointer is not 16-byte aligned");
+    }
+    return FCDP_OK;
+}
+
+fcdp_status check_shard_ptrs(const fcdp_layout *L, const void *const *shard_ptrs, const char *fn)
+{
+    if (!shard_ptrs) return fail(FCDP_EINVAL, std::string(fn) + ": shard_ptrs is NULL");
+    for (int32_t r = 0; r < L->G; ++r) {
+        if (!shard_ptrs[r]) return fail(FCDP_EINVAL, std::string(fn) + ": a shard pointer is NULL");
+        if (!aligned16(shard_ptrs[r])) return fail(FCDP_EALIGN, std::string(fn) + ": a shard pointer is not 16-byte aligned");
+    }
+    return FCDP_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+void fcdp_layout_destroy(fcdp_layout *L)
+{
+    if (!L) return;
+    int cur = -1;
+    const bool have_cur = hipGetDevice(&cur) == hipSuccess;
+    for (auto &d : L->dev) {
+        if (have_cur && d.device != cur) (void)hipSetDevice(d.device);
+        if (d.unflatten) (void)hipFree(d.unflatten);
+        if (d.flatten) (void)hipFree(d.flatten);
+        if (d.pack) (void)hipFree(d.pack);
+        if (d.unpack) (void)hipFree(d.unpack);
+        if (have_cur && d.device != cur) (void)hipSetDevice(cur);
+    }
+    delete L;
+}
+
+fcdp_status fcdp_layout_prepare(const fcdp_layout *L)
+{
+    if (!L) return fail(FCDP_EINVAL, "fcdp_layout_prepare: layout is NULL");
+    const fcdp::DeviceTables *d = nullptr;
+    return tables_for_current_device(L, &d);
+}
+
+fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
+                                   const void *const *shard_ptrs,
+                                   void *host_cache, void *staging,
+                                   void *const *tensor_ptrs, int store_cache,
+                                   fcdp_stream compute_, fcdp_stream copy_)
+{
+    const char *fn = "fcdp_materialize_layer";
+    if (!L) return fail(FCDP_EINVAL, std::string(fn) + ": layout is NULL");
+    if (src != FCDP_SRC_DEVICE_SHARDS && src != FCDP_SRC_HOST_DMA && src != FCDP_SRC_HOST_ZEROCOPY)
+        return fail(FCDP_EINVAL, std::string(fn) + ": unknown source");
+    fcdp_status st = check_tensor_ptrs(L, reinterpret_cast<const void *const *>(tensor_ptrs), fn);
+    if (st != FCDP_OK) return st;
+    hipStream_t compute = static_cast<hipStream_t>(compute_);
+    hipStream_t copy = static_cast<hipStream_t>(copy_);
+    const size_t flat_bytes = static_cast<size_t>(L->N_pad) * L->esz;
+    const size_t shard_bytes = static_cast<size_t>(L->S) * L->esz;
+    void *zc_alias = nullptr;
+    if (src == FCDP_SRC_DEVICE_SHARDS) {
+        if ((st = check_shard_ptrs(L, shard_ptrs, fn)) != FCDP_OK) return st;
+        if (store_cache && !host_cache)
+            return fail(FCDP_EINVAL, std::string(fn) + ": store_cache needs host_cache");
+    } else {
+        if (store_cache)
+            return fail(FCDP_EINVAL, std::string(fn) + ": store_cache is only valid with FCDP_SRC_DEVICE_SHARDS");
+        if (!host_cache) return fail(FCDP_EINVAL, std::string(fn) + ": host_cache is NULL");
+        if (!aligned16(host_cache)) return fail(FCDP_EALIGN, std::string(fn) + ": host_cache is not 16-byte aligned");
+        if (src == FCDP_SRC_HOST_DMA) {
+            if (!staging) return fail(FCDP_EINVAL, std::string(fn) + ": FCDP_SRC_HOST_DMA needs a staging buffer");
+            if (!aligned16(staging)) return fail(FCDP_EALIGN, std::string(fn) + ": staging is not 16-byte aligned");
+        } else if (flat_bytes) {
+            hipPointerAttribute_t attr;
+            std::memset(&attr, 0, sizeof attr);
+            hipError_t e = hipPointerGetAttributes(&attr, host_cache);
+            if (e != hipSuccess) {
+                (void)hipGetLastError(); // clear the sticky error of an unknown pointer
+                return fail(FCDP_ENOTPINNED, std::string(fn) + ": host_cache is not known to HIP as pinned host memory");
+            }
+            if (attr.type != hipMemoryTypeHost || !attr.devicePointer)
+                return fail(FCDP_ENOTPINNED, std::string(fn) + ": host_cache is not mapped pinned host memory");
+            zc_alias = attr.devicePointer;
+        }
+    }
+    if (store_cache && !aligned16(host_cache))
+        return fail(FCDP_EALIGN, std::string(fn) + ": host_cache is not 16-byte aligned");
+    if (L->N == 0 && !(store_cache && flat_bytes)) return FCDP_OK;
+
+    DeviceCtx *ctx = nullptr;
+    if ((st = current_ctx(&ctx)) != FCDP_OK) return st;
+    const fcdp::DeviceTables *tabs = nullptr;
+    if ((st = tables_for_current_device(L, &tabs)) != FCDP_OK) return st;
+    const fcdp::Tuning &tune = fcdp::tuning();
+
+    const void *small[FCDP_MAX_G];
+    if (src == FCDP_SRC_DEVICE_SHARDS) {
+        if (store_cache && flat_bytes) {
+            // H <- concat(shards): after the producers of the shards, beside the scatter
+            if ((st = order_after(ctx, compute, copy)) != FCDP_OK) return st;
+            char *h = static_cast<char *>(host_cache);
+            // contiguous shards (one gather buffer) go out as a single copy
+            bool contiguous = true;
+            for (int32_t r = 1; r < L->G; ++r)
+                if (static_cast<const char *>(shard_ptrs[r]) != static_cast<const char *>(shard_ptrs[0]) + r * shard_bytes)
+                    contiguous = false;
+            if (contiguous) {
+                FCDP_HIP(hipMemcpyAsync(h, shard_ptrs[0], flat_bytes, hipMemcpyDeviceToHost, copy), "hipMemcpyAsync(D2H)");
+            } else {
+                for (int32_t r = 0; r < L->G; ++r)
+                    FCDP_HIP(hipMemcpyAsync(h + r * shard_bytes, shard_ptrs[r], shard_bytes, hipMemcpyDeviceToHost, copy), "hipMemcpyAsync(D2H)");
+            }
+        }
+        for (int32_t r = 0; r < L->G; ++r) small[r] = shard_ptrs[r];
+        return run_windowed(L->unflatten, tabs->unflatten, fcdp::TensorSide::Dst, L->T, small, L->G,
+                            reinterpret_cast<const void *const *>(tensor_ptrs), tune.copy_nt != 0,
+                            tune.copy_wg_per_cu, compute, "launch unflatten");
+    }
+    if (src == FCDP_SRC_HOST_DMA) {
+        DeviceCtx::StagingUse *use = nullptr;
+        if ((st = staging_slot(ctx, staging, &use)) != FCDP_OK) return st;
+        if (use->staging == staging)
+            FCDP_HIP(hipStreamWaitEvent(copy, use->done, 0), "hipStreamWaitEvent(staging)");
+        FCDP_HIP(hipMemcpyAsync(staging, host_cache, flat_bytes, hipMemcpyHostToDevice, copy), "hipMemcpyAsync(H2D)");
+        if ((st = order_after(ctx, copy, compute)) != FCDP_OK) return st;
+        for (int32_t r = 0; r < L->G; ++r) small[r] = static_cast<const char *>(staging) + r * shard_bytes;
+        st = run_windowed(L->unflatten, tabs->unflatten, fcdp::TensorSide::Dst, L->T, small, L->G,
+                          reinterpret_cast<const void *const *>(tensor_ptrs), tune.copy_nt != 0,
+                          tune.copy_wg_per_cu, compute, "launch unflatten");
+        if (st != FCDP_OK) return st;
+        FCDP_HIP(hipEventRecord(use->done, compute), "hipEventRecord(staging)");
+        use->staging = staging;
+        return FCDP_OK;
+    }
+    // zero-copy: the kernel's loads cross the host link
+    if ((st = order_after(ctx, copy, compute)) != FCDP_OK) return st;
+    for (int32_t r = 0; r < L->G; ++r) small[r] = static_cast<const char *>(zc_alias) + r * shard_bytes;
+    return run_windowed(L->unflatten, tabs->unflatten, fcdp::TensorSide::Dst, L->T, small, L->G,
+                        reinterpret_cast<const void *const *>(tensor_ptrs), false,
+                        tune.zc_wg_per_cu, compute, "launch zero-copy unflatten");
+}
+
+fcdp_status fcdp_flatten_to_shards(const fcdp_layout *L, const void *const *tensor_ptrs,
+                                   void *const *shard_ptrs, fcdp_stream stream)
+{
+    const char *fn = "fcdp_flatten_to_shards";
+    if (!L) return fail(FCDP_EINVAL, std::string(fn) + ": layout is NULL");
+    fcdp_status st = check_tensor_ptrs(L, tensor_ptrs, fn);
+    if (st != FCDP_OK) return st;
+    if ((st = check_shard_ptrs(L, reinterpret_cast<const void *const *>(shard_ptrs), fn)) != FCDP_OK) return st;
+    if (L->N_pad == 0) return FCDP_OK;
+    const fcdp::DeviceTables *tabs = nullptr;
+    if ((st = tables_for_current_device(L, &tabs)) != FCDP_OK) return st;
+    const void *small[FCDP_MAX_G];
+    for (int32_t r = 0; r < L->G; ++r) small[r] = shard_ptrs[r];
+    const fcdp::Tuning &tune = fcdp::tuning();
+    return run_windowed(L->flatten, tabs->flatten, fcdp::TensorSide::Src, L->T, small, L->G, tensor_ptrs,
+                        tune.copy_nt != 0, tune.copy_wg_per_cu, static_cast<hipStream_t>(stream), "launch flatten");
+}
+
+fcdp_status fcdp_reduce_grad_shard(const void *const *partial_ptrs, int32_t G, int64_t elem_offset,
+                                   int64_t count, fcdp_dtype in, fcdp_dtype out, void *out_shard,
+                                   fcdp_stream stream)
+{
+    const char *fn = "fcdp_reduce_grad_shard";
+    if (!partial_ptrs) return fail(FCDP_EINVAL, std::string(fn) + ": partial_ptrs is NULL");
+    if (G < 1) return fail(FCDP_EINVAL, std::string(fn) + ": G must be >= 1");
+    if (G > FCDP_MAX_G) return fail(FCDP_ESIZE, std::string(fn) + ": G exceeds FCDP_MAX_G (64)");
+    if (count < 0 || elem_offset < 0) return fail(FCDP_EINVAL, std::string(fn) + ": negative count or offset");
+    if ((in != FCDP_BF16 && in != FCDP_F32) || (out != FCDP_BF16 && out != FCDP_F32))
+        return fail(FCDP_EINVAL, std::string(fn) + ": unknown dtype");
+    if (!out_shard) return fail(FCDP_EINVAL, std::string(fn) + ": out_shard is NULL");
+    if (!aligned16(out_shard)) return fail(FCDP_EALIGN, std::string(fn) + ": out_shard is not 16-byte aligned");
+    const int64_t ie = in == FCDP_F32 ? 4 : 2, oe = out == FCDP_F32 ? 4 : 2;
+    const char *ob = static_cast<const char *>(out_shard);
+    const char *oe_ = ob + count * oe;
+    for (int32_t g = 0; g < G; ++g) {
+        if (!partial_ptrs[g]) return fail(FCDP_EINVAL, std::string(fn) + ": a partial pointer is NULL");
+        if (!aligned16(partial_ptrs[g])) return fail(FCDP_EALIGN, std::string(fn) + ": a partial pointer is not 16-byte aligned");
+        const char *pb = static_cast<const char *>(partial_ptrs[g]) + elem_offset * ie;
+        const char *pe = pb + count * ie;
+        const bool overlap = count > 0 && pb < oe_ && ob < pe;
+        if (overlap && !(pb == ob && ie == oe))
+            return fail(FCDP_EINVAL, std::string(fn) + ": out_shard overlaps an input other than exactly in place");
+    }
+    hipError_t e = static_cast<hipError_t>(fcdp::launch_reduce(partial_ptrs, G, elem_offset, count, in, out, out_shard, stream));
+    if (e != hipSuccess) return hip_fail(e, "launch reduce");
+    return FCDP_OK;
+}
+
+static fcdp_status pack_or_unpack(const fcdp_layout *L, const void *src, void *dst, bool pack,
+                                  fcdp_stream stream, const char *fn)
+{
+    if (!L) return fail(FCDP_EINVAL, std::string(fn) + ": layout is NULL");
+    if (!src || !dst) return fail(FCDP_EINVAL, std::string(fn) + ": NULL buffer");
+    if (!aligned16(src) || !aligned16(dst)) return fail(FCDP_EALIGN, std::string(fn) + ": buffer not 16-byte aligned");
+    const char *flat = static_cast<const char *>(pack ? src : dst);
+    const char *packed = static_cast<const char *>(pack ? dst : src);
+    const int64_t fb = L->N_pad * L->esz, pb = L->N_packed * L->esz;
+    if (fb > 0 && pb > 0 && flat < packed + pb && packed < flat + fb)
+        return fail(FCDP_EINVAL, std::string(fn) + ": flat and packed overlap");
+    const fcdp::PieceTable &tab = pack ? L->pack : L->unpack;
+    if (tab.pieces.empty()) return FCDP_OK;
+    const fcdp::DeviceTables *tabs = nullptr;
+    fcdp_status st = tables_for_current_device(L, &tabs);
+    if (st != FCDP_OK) return st;
+    const void *small[2] = {src, dst};
+    fcdp::CopyLaunch c;
+    c.pieces = pack ? tabs->pack : tabs->unpack;
+    c.n_pieces = static_cast<int64_t>(tab.pieces.size());
+    c.tensor_side = fcdp::TensorSide::None;
+    c.small_ptrs = small;
+    c.n_small = 2;
+    c.nt = false;
+    c.wg_per_cu = 0;
+    hipError_t e = static_cast<hipError_t>(fcdp::launch_copy(c, stream));
+    if (e != hipSuccess) return hip_fail(e, fn);
+    return FCDP_OK;
+}
+
+fcdp_status fcdp_pack_trainable(const fcdp_layout *L, const void *flat, void *packed, fcdp_stream stream)
+{
+    return pack_or_unpack(L, flat, packed, true, stream, "fcdp_pack_trainable");
+}
+
+fcdp_status fcdp_unpack_trainable(const fcdp_layout *L, const void *packed, void *flat, fcdp_stream stream)
+{
+    return pack_or_unpack(L, packed, flat, false, stream, "fcdp_unpack_trainable");
+}
+
+// ------------------------------------------------------------- host cache
+
+fcdp_status fcdp_host_cache_alloc(size_t bytes, int numa_node, void **host, void **dev_alias)
+{
+    const char *fn = "fcdp_host_cache_alloc";
+    if (!host || !dev_alias) return fail(FCDP_EINVAL, std::string(fn) + ": NULL output pointer");
+    *host = nullptr;
+    *dev_alias = nullptr;
+    if (bytes == 0) return fail(FCDP_EINVAL, std::string(fn) + ": zero bytes");
+    if (numa_node >= 1024) return fail(FCDP_EINVAL, std::string(fn) + ": numa_node out of range");
+    unsigned flags = hipHostMallocMapped | hipHostMallocPortable;
+    bool policy_set = false;
+    std::string note;
+#ifdef SYS_set_mempolicy
+    unsigned long mask[16] = {0};
+    if (numa_node >= 0) {
+        mask[numa_node / (8 * sizeof(unsigned long))] |= 1ul << (numa_node % (8 * sizeof(unsigned long)));
+        // MPOL_PREFERRED = 1: take pages from this node while it has any
+        if (syscall(SYS_set_mempolicy, 1, mask, sizeof(mask) * 8) == 0) {
+            policy_set = true;
+            flags |= hipHostMallocNumaUser;
+        } else {
+            note = "fcdp_host_cache_alloc: NUMA policy refused by the kernel; allocated without it";
+        }
+    }
+#else
+    if (numa_node >= 0) note = "fcdp_host_cache_alloc: no NUMA policy call on this platform";
+#endif
+    void *p = nullptr;
+    hipError_t e = hipHostMalloc(&p, bytes, flags);
+#ifdef SYS_set_mempolicy
+    if (policy_set) (void)syscall(SYS_set_mempolicy, 0 /* MPOL_DEFAULT */, nullptr, 0);
+#endif
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(FCDP_ENOMEM, std::string(fn) + ": hipHostMalloc: " + hipGetErrorString(e));
+    }
+    void *d = nullptr;
+    e = hipHostGetDevicePointer(&d, p, 0);
+    if (e != hipSuccess) {
+        (void)hipHostFree(p);
+        return hip_fail(e, "hipHostGetDevicePointer");
+    }
+    *host = p;
+    *dev_alias = d;
+    fcdp::set_error(note);
+    return FCDP_OK;
+}
+
+fcdp_status fcdp_host_cache_free(void *host)
+{
+    if (!host) return FCDP_OK;
+    FCDP_HIP(hipHostFree(host), "hipHostFree");
+    return FCDP_OK;
+}
+
+// ------------------------------------------------------------ dirty state
+} // extern "C"
+
+struct fcdp_cache_state {
+    std::vector<uint8_t> dirty; // [layer][class]
+    int32_t L = 0;
+};
+
+extern "C" {
+
+fcdp_status fcdp_cache_state_create(int32_t n_layers, fcdp_cache_state **out)
+{
+    if (!out) return fail(FCDP_EINVAL, "fcdp_cache_state_create: out is NULL");
+    *out = nullptr;
+    if (n_layers < 1) return fail(FCDP_EINVAL, "fcdp_cache_state_create: n_layers must be >= 1");
+    fcdp_cache_state *s = new (std::nothrow) fcdp_cache_state;
+    if (!s) return fail(FCDP_ENOMEM, "fcdp_cache_state_create: out of host memory");
+    s->L = n_layers;
+    s->dirty.assign(static_cast<size_t>(n_layers) * 2, 1); // Alg. 1: everything starts dirty
+    *out = s;
+    return FCDP_OK;
+}
+
+void fcdp_cache_state_destroy(fcdp_cache_state *s) { delete s; }
+
+static bool host_mode_ok(fcdp_source m) { return m == FCDP_SRC_HOST_DMA || m == FCDP_SRC_HOST_ZEROCOPY; }
+
+fcdp_status fcdp_cache_state_forward_source(fcdp_cache_state *s, int32_t layer, int32_t klass,
+                                            fcdp_source host_mode, fcdp_source *src, int32_t *store_cache)
+{
+    const char *fn = "fcdp_cache_state_forward_source";
+    if (!s || !src || !store_cache) return fail(FCDP_EINVAL, std::string(fn) + ": NULL argument");
+    if (layer < 0 || layer >= s->L || klass < 0 || klass > 1) return fail(FCDP_EINVAL, std::string(fn) + ": layer or class out of range");
+    if (!host_mode_ok(host_mode)) return fail(FCDP_EINVAL, std::string(fn) + ": host_mode must be a host source");
+    uint8_t &d = s->dirty[static_cast<size_t>(layer) * 2 + klass];
+    if (d) {
+        *src = FCDP_SRC_DEVICE_SHARDS; // inter-node gather result, then H <- p
+        *store_cache = 1;
+        d = 0;
+    } else {
+        *src = host_mode;
+        *store_cache = 0;
+    }
+    return FCDP_OK;
+}
+
+fcdp_status fcdp_cache_state_backward_source(const fcdp_cache_state *s, int32_t layer, int32_t klass,
+                                             fcdp_source host_mode, fcdp_source *src)
+{
+    const char *fn = "fcdp_cache_state_backward_source";
+    if (!s || !src) return fail(FCDP_EINVAL, std::string(fn) + ": NULL argument");
+    if (layer < 0 || layer >= s->L || klass < 0 || klass > 1) return fail(FCDP_EINVAL, std::string(fn) + ": layer or class out of range");
+    if (!host_mode_ok(host_mode)) return fail(FCDP_EINVAL, std::string(fn) + ": host_mode must be a host source");
+    if (s->dirty[static_cast<size_t>(layer) * 2 + klass])
+        return fail(FCDP_ESTATE, std::string(fn) + ": backward before the forward pass stored this layer");
+    *src = host_mode;
+    return FCDP_OK;
+}
+
+fcdp_status fcdp_cache_state_optimizer_step(fcdp_cache_state *s)
+{
+    if (!s) return fail(FCDP_EINVAL, "fcdp_cache_state_optimizer_step: NULL state");
+    for (int32_t l = 0; l < s->L; ++l) s->dirty[static_cast<size_t>(l) * 2 + 1] = 1;
+    return FCDP_OK;
+}
+
+int32_t fcdp_cache_state_is_dirty(const fcdp_cache_state *s, int32_t layer, int32_t klass)
+{
+    if (!s || layer < 0 || layer >= s->L || klass < 0 || klass > 1) return -1;
+    return s->dirty[static_cast<size_t>(layer) * 2 + klass];
+}
+
+// ----------------------------------------------------------------- tuning
+
+fcdp_status fcdp_tuning_set(const char *name, int64_t v)
+{
+    if (!name) return fail(FCDP_EINVAL, "fcdp_tuning_set: name is NULL");
+    fcdp::Tuning &t = fcdp::tuning();
+    const std::string n(name);
+    auto pow2 = [](int64_t x) { return x > 0 && (x & (x - 1)) == 0; };
+    if (n == "copy_chunk_bytes") {
+        if (v < 4096 || v > (1 << 24) || v % 4096) return fail(FCDP_EINVAL, "copy_chunk_bytes: multiple of 4096 in 4096..16 MiB");
+        t.copy_chunk_bytes = v;
+    } else if (n == "copy_block") {
+        if (v < 64 || v > 1024 || !pow2(v)) return fail(FCDP_EINVAL, "copy_block: power of two in 64..1024");
+        t.copy_block = v;
+    } else if (n == "copy_unroll") {
+        if (v != 1 && v != 2 && v != 4 && v != 8) return fail(FCDP_EINVAL, "copy_unroll: 1, 2, 4 or 8");
+        t.copy_unroll = v;
+    } else if (n == "copy_wg_per_cu") {
+        if (v < 0 || v > 64) return fail(FCDP_EINVAL, "copy_wg_per_cu: 0..64");
+        t.copy_wg_per_cu = v;
+    } else if (n == "zc_wg_per_cu") {
+        if (v < 0 || v > 64) return fail(FCDP_EINVAL, "zc_wg_per_cu: 0..64");
+        t.zc_wg_per_cu = v;
+    } else if (n == "copy_nt") {
+        if (v != 0 && v != 1) return fail(FCDP_EINVAL, "copy_nt: 0 or 1");
+        t.copy_nt = v;
+    } else if (n == "reduce_block") {
+        if (v < 64 || v > 256 || !pow2(v)) return fail(FCDP_EINVAL, "reduce_block: power of two in 64..256");
+        t.reduce_block = v;
+    } else if (n == "reduce_unroll") {
+        if (v != 1 && v != 2 && v != 4) return fail(FCDP_EINVAL, "reduce_unroll: 1, 2 or 4");
+        t.reduce_unroll = v;
+    } else if (n == "reduce_nt") {
+        if (v != 0 && v != 1) return fail(FCDP_EINVAL, "reduce_nt: 0 or 1");
+        t.reduce_nt = v;
+    } else {
+        return fail(FCDP_EINVAL, "fcdp_tuning_set: unknown knob " + n);
+    }
+    return FCDP_OK;
+}
+
+int64_t fcdp_tuning_get(const char *name)
+{
+    if (!name) return -1;
+    const fcdp::Tuning &t = fcdp::tuning();
+    const std::string n(name);
+    if (n == "copy_chunk_bytes") return t.copy_chunk_bytes;
+    if (n == "copy_block") return t.copy_block;
+    if (n == "copy_unroll") return t.copy_unroll;
+    if (n == "copy_wg_per_cu") return t.copy_wg_per_cu;
+    if (n == "zc_wg_per_cu") return t.zc_wg_per_cu;
+    if (n == "copy_nt") return t.copy_nt;
+    if (n == "reduce_block") return t.reduce_block;
+    if (n == "reduce_unroll") return t.reduce_unroll;
+    if (n == "reduce_nt") return t.reduce_nt;
+    return -1;
+}
+
+fcdp_status fcdp_probe_copy(void *dst, const void *src, size_t bytes, fcdp_stream stream)
+{
+    if (!dst || !src) return fail(FCDP_EINVAL, "fcdp_probe_copy: NULL buffer");
+    if (!aligned16(dst) || !aligned16(src)) return fail(FCDP_EALIGN, "fcdp_probe_copy: buffer not 16-byte aligned");
+    if (bytes & 1) return fail(FCDP_EINVAL, "fcdp_probe_copy: bytes must be even");
+    hipError_t e = static_cast<hipError_t>(fcdp::launch_plain_copy(dst, src, bytes, stream));
+    if (e != hipSuccess) return hip_fail(e, "launch plain copy");
+    return FCDP_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,114 @@
+// Internal declarations shared by the host-side translation units of libfcdp.
+#ifndef FCDP_INTERNAL_H
+#define FCDP_INTERNAL_H
+
+#include <cstdint>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "fcdp.h"
+
+namespace fcdp {
+
+// One unit of copy work: nbytes bytes from buffer src_idx at byte offset
+// src_off to buffer dst_idx at byte offset dst_off.  src_idx < 0 means "write
+// zeros".  A piece never crosses a tensor, shard or chunk boundary, so every
+// workgroup moves a bounded, nearly equal number of bytes.
+struct Piece {
+    int64_t src_off;
+    int64_t dst_off;
+    int32_t nbytes;
+    int32_t src_idx;
+    int32_t dst_idx;
+    int32_t reserved;
+};
+static_assert(sizeof(Piece) == 32, "Piece must stay 32 bytes");
+
+// Which side of a piece table indexes the (possibly long) per-tensor pointer
+// list; the other side indexes the short list (shards, or a single buffer).
+enum class TensorSide { Dst, Src, None };
+
+struct PieceTable {
+    std::vector<Piece> pieces;
+    // For tables whose tensor side can exceed one launch's pointer window:
+    // [win_begin[w], win_begin[w+1]) are the pieces whose tensor index lies in
+    // window w (tensors [w*kTensorWindow, (w+1)*kTensorWindow)).
+    std::vector<int64_t> win_begin;
+};
+
+constexpr int kTensorWindow = 256; // per-launch tensor pointers (kernarg)
+constexpr int kMaxDevices = 16;
+
+struct DeviceTables {
+    int device = -1;
+    Piece *unflatten = nullptr;
+    Piece *flatten = nullptr;
+    Piece *pack = nullptr;
+    Piece *unpack = nullptr;
+};
+
+struct Segment {
+    int64_t t, r, dst_off, src_off, len;
+};
+
+} // namespace fcdp
+
+struct fcdp_layout {
+    int32_t T = 0, G = 1, esz = 2, q = 64;
+    int64_t N = 0, N_pad = 0, S = 0, N_t = 0, N_packed = 0;
+    int64_t chunk_bytes = 0;
+    std::vector<int64_t> numel, off;
+    std::vector<uint8_t> trainable;
+    std::vector<fcdp::Segment> segments;
+    fcdp::PieceTable unflatten, flatten, pack, unpack;
+    // device copies, filled lazily per device
+    mutable std::mutex mu;
+    mutable std::vector<fcdp::DeviceTables> dev;
+};
+
+namespace fcdp {
+
+void set_error(const std::string &msg);
+const std::string &last_error_ref();
+fcdp_status fail(fcdp_status st, const std::string &msg);
+
+// tuning knobs (see fcdp_tuning_set)
+struct Tuning {
+    int64_t copy_chunk_bytes = 65536; // piece size cap; multiple of 4096
+    int64_t copy_block = 256;         // threads per workgroup: 64..1024
+    int64_t copy_unroll = 4;          // 16-byte vectors in flight per thread
+    int64_t copy_wg_per_cu = 0;       // 0 = one workgroup per piece
+    int64_t copy_nt = 1;              // non-temporal loads/stores
+    int64_t zc_wg_per_cu = 0;         // same, for the zero-copy fetch
+    int64_t reduce_block = 256;
+    int64_t reduce_unroll = 2;        // vectors per thread
+    int64_t reduce_nt = 1;
+};
+Tuning &tuning();
+
+// host-side table construction (fcdp_layout.cpp)
+fcdp_status build_tables(fcdp_layout *L);
+
+// kernel launchers (fcdp_kernels.hip).  All return a hipError_t as int.
+struct CopyLaunch {
+    const Piece *pieces = nullptr;  // device
+    int64_t n_pieces = 0;
+    TensorSide tensor_side = TensorSide::None;
+    int32_t tensor_base = 0;        // first tensor index of this window
+    const void *const *small_ptrs = nullptr; // host array, n_small entries
+    int32_t n_small = 0;
+    const void *const *tensor_ptrs = nullptr; // host array (window start)
+    int32_t n_tensor = 0;
+    bool nt = true;
+    int64_t wg_per_cu = 0;
+};
+int launch_copy(const CopyLaunch &c, void *stream);
+int launch_reduce(const void *const *partials, int32_t G, int64_t elem_offset,
+                  int64_t count, int in_dtype, int out_dtype, void *out,
+                  void *stream);
+int launch_plain_copy(void *dst, const void *src, size_t bytes, void *stream);
+int device_cu_count();
+
+} // namespace fcdp
+#endif

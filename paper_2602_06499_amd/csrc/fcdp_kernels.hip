@@ -1,0 +1,508 @@
+// HIP kernels of libfcdp for gfx950 (MI355X) and their launchers.
+//
+//   copy_pieces  -- the scatter/gather engine behind unflatten (shards ->
+//                   tensors, from HBM or straight from mapped host memory),
+//                   flatten, pack and unpack.  Pure byte movement, bound by
+//                   HBM (or by the host link when the source is host memory).
+//   reduce_ranks -- rank-order fp32 sum of G partial gradient slices with an
+//                   optional bf16 (nearest-even) store.  Bound by HBM reads.
+//   plain_copy   -- contiguous copy with the same inner loop; the known-size
+//                   reference for counter calibration.
+//
+// Nothing here is a contraction, so no MFMA and no LDS staging: every byte is
+// read once and written once, there is no reuse to stage.  What matters is
+// 16-byte coalesced access per lane, enough independent loads in flight per
+// wave to cover HBM latency, and equal bytes per workgroup.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "fcdp_internal.h"
+
+namespace fcdp {
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// 16-byte vectors that are only 4- or 2-byte aligned: the compiler picks the
+// widest access the target allows for that alignment.
+typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint32_t u32x4_a2 __attribute__((ext_vector_type(4), aligned(2)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2_a2 __attribute__((ext_vector_type(2), aligned(2)));
+
+constexpr int kMaxSmall = FCDP_MAX_G;
+
+struct CopyArgs {
+    const Piece *pieces;
+    int64_t n_pieces;
+    int32_t tensor_base;
+    int32_t tensor_side; // 0 dst, 1 src, 2 none
+    char *small_ptrs[kMaxSmall];
+    char *tensor_ptrs[kTensorWindow];
+};
+
+template <typename V, bool NT>
+__device__ __forceinline__ u32x4 load16(const char *p)
+{
+    const V *vp = reinterpret_cast<const V *>(p);
+    if constexpr (NT) {
+        V v = __builtin_nontemporal_load(vp);
+        return u32x4{v.x, v.y, v.z, v.w};
+    } else {
+        V v = *vp;
+        return u32x4{v.x, v.y, v.z, v.w};
+    }
+}
+
+template <bool NT>
+__device__ __forceinline__ void store16(char *p, u32x4 v)
+{
+    u32x4 *vp = reinterpret_cast<u32x4 *>(p);
+    if constexpr (NT)
+        __builtin_nontemporal_store(v, vp);
+    else
+        *vp = v;
+}
+
+// Copies nvec 16-byte vectors from s to d; d is 16-byte aligned, s is aligned
+// as V says.  UNROLL independent loads are issued per thread before the
+// first store.
+template <typename V, int UNROLL, bool NT>
+__device__ __forceinline__ void copy_body(const char *s, char *d, uint32_t nvec,
+                                          uint32_t tid, uint32_t nthreads)
+{
+    const uint32_t step = nthreads * UNROLL;
+    uint32_t base = 0;
+    for (; base + step <= nvec; base += step) {
+        u32x4 r[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            r[u] = load16<V, NT>(s + (size_t)(base + u * nthreads + tid) * 16);
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            store16<NT>(d + (size_t)(base + u * nthreads + tid) * 16, r[u]);
+    }
+    if (base < nvec) {
+        u32x4 r[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const uint32_t i = base + u * nthreads + tid;
+            if (i < nvec) r[u] = load16<V, NT>(s + (size_t)i * 16);
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const uint32_t i = base + u * nthreads + tid;
+            if (i < nvec) store16<NT>(d + (size_t)i * 16, r[u]);
+        }
+    }
+}
+
+template <int UNROLL, bool NT>
+__device__ __forceinline__ void zero_body(char *d, uint32_t nvec, uint32_t tid,
+                                          uint32_t nthreads)
+{
+    for (uint32_t i = tid; i < nvec; i += nthreads)
+        store16<NT>(d + (size_t)i * 16, u32x4{0u, 0u, 0u, 0u});
+}
+
+// One piece: n bytes (even), s and d both at least 2-byte aligned.
+template <int UNROLL, bool NT>
+__device__ __forceinline__ void copy_piece(const char *s, char *d, uint32_t n,
+                                           bool zero, uint32_t tid,
+                                           uint32_t nthreads)
+{
+    // head: 2-byte units until d reaches a 16-byte boundary
+    uint32_t head = static_cast<uint32_t>((16u - (reinterpret_cast<uintptr_t>(d) & 15u)) & 15u);
+    if (head > n) head = n;
+    if (tid < (head >> 1)) {
+        uint16_t v = zero ? uint16_t(0) : reinterpret_cast<const uint16_t *>(s)[tid];
+        reinterpret_cast<uint16_t *>(d)[tid] = v;
+    }
+    s += head;
+    d += head;
+    n -= head;
+    const uint32_t nvec = n >> 4;
+    if (zero) {
+        zero_body<UNROLL, NT>(d, nvec, tid, nthreads);
+    } else {
+        const uint32_t mis = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(s) & 15u);
+        if (mis == 0)
+            copy_body<u32x4, UNROLL, NT>(s, d, nvec, tid, nthreads);
+        else if ((mis & 3u) == 0)
+            copy_body<u32x4_a4, UNROLL, NT>(s, d, nvec, tid, nthreads);
+        else
+            copy_body<u32x4_a2, UNROLL, NT>(s, d, nvec, tid, nthreads);
+    }
+    // tail: the last n % 16 bytes, 2-byte units
+    const uint32_t done = nvec << 4;
+    const uint32_t tail = n - done;
+    if (tid < (tail >> 1)) {
+        uint16_t v = zero ? uint16_t(0)
+                          : reinterpret_cast<const uint16_t *>(s + done)[tid];
+        reinterpret_cast<uint16_t *>(d + done)[tid] = v;
+    }
+}
+
+__device__ __forceinline__ int32_t uniform32(int32_t v)
+{
+    return __builtin_amdgcn_readfirstlane(v);
+}
+
+__device__ __forceinline__ int64_t uniform64(int64_t v)
+{
+    const uint32_t lo = static_cast<uint32_t>(uniform32(static_cast<int32_t>(v)));
+    const uint32_t hi = static_cast<uint32_t>(uniform32(static_cast<int32_t>(v >> 32)));
+    return static_cast<int64_t>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+
+template <int UNROLL, bool NT>
+__global__ void copy_pieces(const CopyArgs a)
+{
+    const uint32_t tid = threadIdx.x;
+    const uint32_t nthreads = blockDim.x;
+    for (int64_t pi = blockIdx.x; pi < a.n_pieces; pi += gridDim.x) {
+        // Every lane reads the same piece record; moving its fields to
+        // scalar registers keeps the pointer look-ups and the address
+        // arithmetic below on the scalar unit.
+        const Piece p = a.pieces[pi];
+        const int32_t src_idx = uniform32(p.src_idx);
+        const int32_t dst_idx = uniform32(p.dst_idx);
+        const int64_t src_off = uniform64(p.src_off);
+        const int64_t dst_off = uniform64(p.dst_off);
+        const uint32_t nbytes = static_cast<uint32_t>(uniform32(p.nbytes));
+        const bool zero = src_idx < 0;
+        const char *s = nullptr;
+        char *d;
+        if (a.tensor_side == 0) {
+            d = a.tensor_ptrs[dst_idx - a.tensor_base];
+            if (!zero) s = a.small_ptrs[src_idx];
+        } else if (a.tensor_side == 1) {
+            d = a.small_ptrs[dst_idx];
+            if (!zero) s = a.tensor_ptrs[src_idx - a.tensor_base];
+        } else {
+            d = a.small_ptrs[1];
+            if (!zero) s = a.small_ptrs[0];
+        }
+        copy_piece<UNROLL, NT>(zero ? nullptr : s + src_off, d + dst_off,
+                               nbytes, zero, tid, nthreads);
+    }
+}
+
+template <int UNROLL, bool NT>
+__global__ void plain_copy(const char *__restrict__ src, char *__restrict__ dst,
+                           size_t bytes, uint32_t chunk)
+{
+    const size_t n_chunks = (bytes + chunk - 1) / chunk;
+    for (size_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+        const size_t o = c * chunk;
+        const uint32_t n = static_cast<uint32_t>(bytes - o < chunk ? bytes - o : chunk);
+        copy_piece<UNROLL, NT>(src + o, dst + o, n, false, threadIdx.x, blockDim.x);
+    }
+}
+
+// ------------------------------------------------------------------ reduce
+
+struct ReduceArgs {
+    const char *p[FCDP_MAX_G]; // already offset to the slice start
+    char *out;
+    int64_t count;
+    int32_t G;
+};
+
+__device__ __forceinline__ uint32_t bf16_rne_bits(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x0040u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// Loads four consecutive elements of partial g as fp32.
+template <bool IN_F32, bool ALIGNED, bool NT>
+__device__ __forceinline__ void load4(const char *base, int64_t vec, float (&v)[4])
+{
+    if constexpr (IN_F32) {
+        const char *p = base + vec * 16;
+        u32x4 r;
+        if constexpr (ALIGNED)
+            r = load16<u32x4, NT>(p);
+        else
+            r = load16<u32x4_a4, NT>(p);
+        v[0] = __uint_as_float(r.x);
+        v[1] = __uint_as_float(r.y);
+        v[2] = __uint_as_float(r.z);
+        v[3] = __uint_as_float(r.w);
+    } else {
+        const char *p = base + vec * 8;
+        u32x2 r;
+        if constexpr (ALIGNED) {
+            const u32x2 *vp = reinterpret_cast<const u32x2 *>(p);
+            if constexpr (NT) r = __builtin_nontemporal_load(vp);
+            else r = *vp;
+        } else {
+            const u32x2_a2 *vp = reinterpret_cast<const u32x2_a2 *>(p);
+            u32x2_a2 t = *vp;
+            r = u32x2{t.x, t.y};
+        }
+        v[0] = __uint_as_float(r.x << 16);
+        v[1] = __uint_as_float(r.x & 0xffff0000u);
+        v[2] = __uint_as_float(r.y << 16);
+        v[3] = __uint_as_float(r.y & 0xffff0000u);
+    }
+}
+
+template <bool OUT_F32, bool NT>
+__device__ __forceinline__ void store4(char *out, int64_t vec, const float (&a)[4])
+{
+    if constexpr (OUT_F32) {
+        u32x4 r{__float_as_uint(a[0]), __float_as_uint(a[1]),
+                __float_as_uint(a[2]), __float_as_uint(a[3])};
+        store16<NT>(out + vec * 16, r);
+    } else {
+        u32x2 r{bf16_rne_bits(a[0]) | (bf16_rne_bits(a[1]) << 16),
+                bf16_rne_bits(a[2]) | (bf16_rne_bits(a[3]) << 16)};
+        u32x2 *vp = reinterpret_cast<u32x2 *>(out + vec * 8);
+        if constexpr (NT) __builtin_nontemporal_store(r, vp);
+        else *vp = r;
+    }
+}
+
+constexpr int kGroup = 8; // partials loaded back to back before the adds
+
+// Each thread owns UNROLL groups of four consecutive elements.  The G loads
+// of a group are independent; the adds run strictly in rank order, one
+// binary32 rounding each, so the result does not depend on the launch shape.
+template <bool IN_F32, bool OUT_F32, bool ALIGNED, int UNROLL, bool NT>
+__global__ void __launch_bounds__(256) reduce_ranks(const ReduceArgs a)
+{
+    const int64_t nvec = a.count >> 2;
+    const int64_t per_block = static_cast<int64_t>(blockDim.x) * UNROLL;
+    for (int64_t b0 = static_cast<int64_t>(blockIdx.x) * per_block; b0 < nvec;
+         b0 += static_cast<int64_t>(gridDim.x) * per_block) {
+        float acc[UNROLL][4];
+        int64_t idx[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            idx[u] = b0 + static_cast<int64_t>(u) * blockDim.x + threadIdx.x;
+            if (idx[u] < nvec) load4<IN_F32, ALIGNED, NT>(a.p[0], idx[u], acc[u]);
+        }
+        int g = 1;
+        for (; g + kGroup <= a.G; g += kGroup) {
+            float v[kGroup][UNROLL][4];
+#pragma unroll
+            for (int k = 0; k < kGroup; ++k)
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u)
+                    if (idx[u] < nvec)
+                        load4<IN_F32, ALIGNED, NT>(a.p[g + k], idx[u], v[k][u]);
+#pragma unroll
+            for (int k = 0; k < kGroup; ++k)
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) acc[u][c] = acc[u][c] + v[k][u][c];
+        }
+        if (g < a.G) {
+            const int rem = a.G - g; // 1..kGroup-1, wave-uniform
+            float v[kGroup - 1][UNROLL][4];
+#pragma unroll
+            for (int k = 0; k < kGroup - 1; ++k)
+                if (k < rem)
+#pragma unroll
+                    for (int u = 0; u < UNROLL; ++u)
+                        if (idx[u] < nvec)
+                            load4<IN_F32, ALIGNED, NT>(a.p[g + k], idx[u], v[k][u]);
+#pragma unroll
+            for (int k = 0; k < kGroup - 1; ++k)
+                if (k < rem)
+#pragma unroll
+                    for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+                            acc[u][c] = acc[u][c] + v[k][u][c];
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            if (idx[u] < nvec) store4<OUT_F32, NT>(a.out, idx[u], acc[u]);
+    }
+    // the last count % 4 elements, one thread each
+    const int64_t done = nvec << 2;
+    const int64_t k = done + threadIdx.x;
+    if (blockIdx.x == 0 && k < a.count) {
+        float acc;
+        if constexpr (IN_F32)
+            acc = reinterpret_cast<const float *>(a.p[0])[k];
+        else
+            acc = __uint_as_float(static_cast<uint32_t>(
+                      reinterpret_cast<const uint16_t *>(a.p[0])[k]) << 16);
+        for (int g = 1; g < a.G; ++g) {
+            float v;
+            if constexpr (IN_F32)
+                v = reinterpret_cast<const float *>(a.p[g])[k];
+            else
+                v = __uint_as_float(static_cast<uint32_t>(
+                        reinterpret_cast<const uint16_t *>(a.p[g])[k]) << 16);
+            acc = acc + v;
+        }
+        if constexpr (OUT_F32)
+            reinterpret_cast<float *>(a.out)[k] = acc;
+        else
+            reinterpret_cast<uint16_t *>(a.out)[k] =
+                static_cast<uint16_t>(bf16_rne_bits(acc));
+    }
+}
+
+int g_cu_count[kMaxDevices] = {0};
+
+template <int UNROLL, bool NT>
+hipError_t launch_copy_t(const CopyArgs &args, dim3 grid, dim3 block, hipStream_t st)
+{
+    hipLaunchKernelGGL((copy_pieces<UNROLL, NT>), grid, block, 0, st, args);
+    return hipGetLastError();
+}
+
+template <bool IN_F32, bool OUT_F32, bool ALIGNED>
+hipError_t launch_reduce_t(const ReduceArgs &args, dim3 grid, dim3 block,
+                           int unroll, bool nt, hipStream_t st)
+{
+#define FCDP_RED(U, N)                                                         \
+    hipLaunchKernelGGL((reduce_ranks<IN_F32, OUT_F32, ALIGNED, U, N>), grid,   \
+                       block, 0, st, args)
+    if (nt) {
+        if (unroll >= 4) FCDP_RED(4, true);
+        else if (unroll >= 2) FCDP_RED(2, true);
+        else FCDP_RED(1, true);
+    } else {
+        if (unroll >= 4) FCDP_RED(4, false);
+        else if (unroll >= 2) FCDP_RED(2, false);
+        else FCDP_RED(1, false);
+    }
+#undef FCDP_RED
+    return hipGetLastError();
+}
+
+} // namespace
+
+int device_cu_count()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (dev < 0 || dev >= kMaxDevices) return 256;
+    if (g_cu_count[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        g_cu_count[dev] = n;
+    }
+    return g_cu_count[dev];
+}
+
+int launch_copy(const CopyLaunch &c, void *stream)
+{
+    if (c.n_pieces <= 0) return hipSuccess;
+    CopyArgs args;
+    args.pieces = c.pieces;
+    args.n_pieces = c.n_pieces;
+    args.tensor_base = c.tensor_base;
+    args.tensor_side = c.tensor_side == TensorSide::Dst ? 0
+                       : c.tensor_side == TensorSide::Src ? 1 : 2;
+    for (int i = 0; i < kMaxSmall; ++i)
+        args.small_ptrs[i] = i < c.n_small
+            ? const_cast<char *>(static_cast<const char *>(c.small_ptrs[i])) : nullptr;
+    for (int i = 0; i < kTensorWindow; ++i)
+        args.tensor_ptrs[i] = i < c.n_tensor
+            ? const_cast<char *>(static_cast<const char *>(c.tensor_ptrs[i])) : nullptr;
+    const Tuning &t = tuning();
+    int64_t grid = c.n_pieces;
+    if (c.wg_per_cu > 0)
+        grid = std::min<int64_t>(grid, c.wg_per_cu * device_cu_count());
+    grid = std::min<int64_t>(grid, 0x7fffffff);
+    const dim3 g(static_cast<unsigned>(grid)), b(static_cast<unsigned>(t.copy_block));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int unroll = static_cast<int>(t.copy_unroll);
+    if (c.nt) {
+        if (unroll >= 8) return launch_copy_t<8, true>(args, g, b, st);
+        if (unroll >= 4) return launch_copy_t<4, true>(args, g, b, st);
+        if (unroll >= 2) return launch_copy_t<2, true>(args, g, b, st);
+        return launch_copy_t<1, true>(args, g, b, st);
+    }
+    if (unroll >= 8) return launch_copy_t<8, false>(args, g, b, st);
+    if (unroll >= 4) return launch_copy_t<4, false>(args, g, b, st);
+    if (unroll >= 2) return launch_copy_t<2, false>(args, g, b, st);
+    return launch_copy_t<1, false>(args, g, b, st);
+}
+
+int launch_plain_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (bytes == 0) return hipSuccess;
+    const Tuning &t = tuning();
+    const uint32_t chunk = static_cast<uint32_t>(t.copy_chunk_bytes);
+    size_t n_chunks = (bytes + chunk - 1) / chunk;
+    int64_t grid = static_cast<int64_t>(std::min<size_t>(n_chunks, 0x7fffffff));
+    if (t.copy_wg_per_cu > 0)
+        grid = std::min<int64_t>(grid, t.copy_wg_per_cu * device_cu_count());
+    const dim3 g(static_cast<unsigned>(grid)), b(static_cast<unsigned>(t.copy_block));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const char *s = static_cast<const char *>(src);
+    char *d = static_cast<char *>(dst);
+    const int unroll = static_cast<int>(t.copy_unroll);
+#define FCDP_PC(U, N) hipLaunchKernelGGL((plain_copy<U, N>), g, b, 0, st, s, d, bytes, chunk)
+    if (t.copy_nt) {
+        if (unroll >= 8) FCDP_PC(8, true);
+        else if (unroll >= 4) FCDP_PC(4, true);
+        else if (unroll >= 2) FCDP_PC(2, true);
+        else FCDP_PC(1, true);
+    } else {
+        if (unroll >= 8) FCDP_PC(8, false);
+        else if (unroll >= 4) FCDP_PC(4, false);
+        else if (unroll >= 2) FCDP_PC(2, false);
+        else FCDP_PC(1, false);
+    }
+#undef FCDP_PC
+    return hipGetLastError();
+}
+
+int launch_reduce(const void *const *partials, int32_t G, int64_t elem_offset,
+                  int64_t count, int in_dtype, int out_dtype, void *out,
+                  void *stream)
+{
+    if (count <= 0) return hipSuccess;
+    const int64_t in_esz = in_dtype == FCDP_F32 ? 4 : 2;
+    ReduceArgs args;
+    bool aligned = true;
+    for (int g = 0; g < FCDP_MAX_G; ++g) {
+        if (g < G) {
+            args.p[g] = static_cast<const char *>(partials[g]) + elem_offset * in_esz;
+            if (reinterpret_cast<uintptr_t>(args.p[g]) & 15u) aligned = false;
+        } else {
+            args.p[g] = nullptr;
+        }
+    }
+    args.out = static_cast<char *>(out);
+    args.count = count;
+    args.G = G;
+    const Tuning &t = tuning();
+    const int unroll = static_cast<int>(t.reduce_unroll);
+    const int64_t block = t.reduce_block;
+    const int64_t nvec = count >> 2;
+    int64_t grid = (nvec + block * unroll - 1) / (block * unroll);
+    grid = std::max<int64_t>(1, std::min<int64_t>(grid, 0x7fffffff));
+    const dim3 g(static_cast<unsigned>(grid)), b(static_cast<unsigned>(block));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool nt = t.reduce_nt != 0;
+    const bool inf = in_dtype == FCDP_F32, outf = out_dtype == FCDP_F32;
+    if (inf && outf)
+        return aligned ? launch_reduce_t<true, true, true>(args, g, b, unroll, nt, st)
+                       : launch_reduce_t<true, true, false>(args, g, b, unroll, nt, st);
+    if (inf && !outf)
+        return aligned ? launch_reduce_t<true, false, true>(args, g, b, unroll, nt, st)
+                       : launch_reduce_t<true, false, false>(args, g, b, unroll, nt, st);
+    if (!inf && outf)
+        return aligned ? launch_reduce_t<false, true, true>(args, g, b, unroll, nt, st)
+                       : launch_reduce_t<false, true, false>(args, g, b, unroll, nt, st);
+    return aligned ? launch_reduce_t<false, false, true>(args, g, b, unroll, nt, st)
+                   : launch_reduce_t<false, false, false>(args, g, b, unroll, nt, st);
+}
+
+} // namespace fcdp

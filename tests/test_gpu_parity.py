@@ -1,0 +1,408 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Bit-exact for every copy/pack/index operation and
+for the rank-order fp32 reduction (NaN lanes: NaN-ness only)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2602_06499_amd as fcdp
+from paper_2602_06499_amd import synth
+from gpu_util import Arena, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def _rand_tensors(seed, sizes, dtype):
+    g = synth.rng(0, seed, synth.KIND_MISC, 21)
+    info = np.iinfo(dtype)
+    return [g.integers(0, int(info.max) + 1, size=k, dtype=dtype) for k in sizes]
+
+
+def _layer_cases():
+    cases = []
+    for G in (1, 2, 3, 4, 8, 16, 32, 64):
+        for k, esz in enumerate((2, 4)):
+            sizes = synth.random_layer(4000 + G * 3 + k, T=7 + G % 5, max_numel=70000)
+            cases.append(("rand_G%d_e%d" % (G, esz), sizes, G, esz))
+    cases.append(("tiny_padding_only_shards", [3, 0, 1], 8, 2))
+    cases.append(("single_element", [1], 4, 2))
+    cases.append(("zeros_and_one", [0, 0, 5, 0], 3, 4))
+    cases.append(("aligned_multi_tile", [8 * 40000, 8 * 1000, 8 * 123457], 4, 2))
+    cases.append(("odd_multi_tile", [300001, 7, 65537, 131075], 3, 2))
+    cases.append(("many_tensors", [(i * 37) % 501 for i in range(600)], 5, 2))
+    return cases
+
+
+CASES = _layer_cases()
+
+
+@pytest.mark.parametrize("name,sizes,G,esz", CASES, ids=[c[0] for c in CASES])
+@pytest.mark.parametrize("contiguous", [False, True])
+def test_unflatten_and_flatten(name, sizes, G, esz, contiguous):
+    dt = np.uint16 if esz == 2 else np.uint32
+    tensors = _rand_tensors(len(sizes) + G, sizes, dt)
+    flat = oracle.flatten(tensors, G)
+    shards = oracle.split(flat, G)
+    want = oracle.materialize_from_shards(shards, sizes)
+    L = fcdp.fcdp_layout_build(sizes, None, G, esz)
+    S = L.shard_numel
+    assert S == shards[0].size
+    if contiguous:
+        sh_arena = Arena([S * esz * G])
+        sh_arena.fill(0, flat)
+        sh_ptrs = [sh_arena.ptr(0) + r * S * esz for r in range(G)]
+    else:
+        sh_arena = Arena([S * esz] * G)
+        for r in range(G):
+            sh_arena.fill(r, shards[r])
+        sh_ptrs = sh_arena.ptrs()
+    out = Arena([k * esz for k in sizes])
+    fcdp.fcdp_materialize_layer(L, fcdp.SRC_DEVICE_SHARDS, sh_ptrs, None, None,
+                                out.ptrs(), False, None, None)
+    torch.cuda.synchronize()
+    for t in range(len(sizes)):
+        assert np.array_equal(out.get(t, dt), want[t]), (name, t)
+    out.check_guards()
+    sh_arena.check_guards()
+    # inverse: tensors -> shards with zero tail padding
+    back = Arena([S * esz] * G)
+    fcdp.fcdp_flatten_to_shards(L, out.ptrs(), back.ptrs(), None)
+    torch.cuda.synchronize()
+    for r in range(G):
+        assert np.array_equal(back.get(r, dt), shards[r]), (name, r)
+    back.check_guards()
+
+
+@pytest.mark.parametrize("name,sizes,G,esz", CASES[::3] + CASES[-6:], ids=[c[0] for c in CASES[::3] + CASES[-6:]])
+def test_host_cache_store_and_fetch(name, sizes, G, esz):
+    """Store on a miss, then both host sources give the same tensors as the
+    device source (the cache-hit path equals the cache-miss path)."""
+    dt = np.uint16 if esz == 2 else np.uint32
+    tensors = _rand_tensors(len(sizes) * 3 + G, sizes, dt)
+    flat = oracle.flatten(tensors, G)
+    shards = oracle.split(flat, G)
+    want = oracle.materialize_from_shards(shards, sizes)
+    L = fcdp.fcdp_layout_build(sizes, None, G, esz)
+    S, Np = L.shard_numel, L.padded_numel
+    sh = Arena([S * esz] * G)
+    for r in range(G):
+        sh.fill(r, shards[r])
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    H = fcdp.fcdp_host_cache_alloc(max(Np * esz, 16))
+    H.numpy(np.uint8)[:] = 0x77
+    out0 = Arena([k * esz for k in sizes])
+    fcdp.fcdp_materialize_layer(L, fcdp.SRC_DEVICE_SHARDS, sh.ptrs(), H, None,
+                                out0.ptrs(), True, compute, copy)
+    torch.cuda.synchronize()
+    assert np.array_equal(H.numpy(dt, Np), oracle.cache_store(shards))
+    assert np.array_equal(H.numpy(dt, Np), flat)
+    for mode in (fcdp.SRC_HOST_DMA, fcdp.SRC_HOST_ZEROCOPY):
+        out = Arena([k * esz for k in sizes])
+        staging = Arena([Np * esz]) if mode == fcdp.SRC_HOST_DMA else None
+        fcdp.fcdp_materialize_layer(L, mode, None, H,
+                                    staging.ptr(0) if staging else None,
+                                    out.ptrs(), False, compute, copy)
+        torch.cuda.synchronize()
+        for t in range(len(sizes)):
+            assert np.array_equal(out.get(t, dt), want[t]), (name, mode, t)
+        out.check_guards()
+        if staging:
+            staging.check_guards()
+    H.free()
+
+
+REDUCE_CASES = [
+    # G, count, elem_offset, in, out
+    (1, 1000, 0, oracle.F32, oracle.F32),
+    (2, 4099, 0, oracle.F32, oracle.F32),
+    (3, 70001, 5, oracle.F32, oracle.BF16),
+    (4, 1 << 18, 0, oracle.F32, oracle.F32),
+    (7, 33333, 3, oracle.F32, oracle.F32),
+    (8, 300007, 0, oracle.F32, oracle.BF16),
+    (9, 12345, 1, oracle.F32, oracle.F32),
+    (15, 5000, 2, oracle.F32, oracle.BF16),
+    (16, 65536 + 3, 0, oracle.F32, oracle.F32),
+    (17, 40000, 7, oracle.F32, oracle.F32),
+    (32, 100003, 0, oracle.F32, oracle.BF16),
+    (33, 2049, 0, oracle.F32, oracle.F32),
+    (64, 30001, 11, oracle.F32, oracle.F32),
+    (1, 777, 1, oracle.BF16, oracle.BF16),
+    (4, 50001, 0, oracle.BF16, oracle.F32),
+    (8, 262147, 3, oracle.BF16, oracle.BF16),
+    (32, 9999, 5, oracle.BF16, oracle.F32),
+    (5, 3, 0, oracle.F32, oracle.F32),
+    (5, 0, 0, oracle.F32, oracle.F32),
+]
+
+
+def _cmp_reduce(got, want, out_dtype):
+    if out_dtype == oracle.F32:
+        nan = np.isnan(want)
+        assert np.array_equal(np.isnan(got), nan)
+        assert np.array_equal(got.view(np.uint32)[~nan], want.view(np.uint32)[~nan])
+    else:
+        nan = ((want & 0x7F80) == 0x7F80) & ((want & 0x7F) != 0)
+        gnan = ((got & 0x7F80) == 0x7F80) & ((got & 0x7F) != 0)
+        assert np.array_equal(gnan, nan)
+        assert np.array_equal(got[~nan], want[~nan])
+
+
+@pytest.mark.parametrize("G,count,e0,in_dt,out_dt", REDUCE_CASES)
+def test_reduce_parity(G, count, e0, in_dt, out_dt):
+    g = synth.rng(0, 900 + G, synth.KIND_GRAD, count % 1000)
+    total = e0 + count + 13
+    parts = []
+    for r in range(G):
+        x = g.standard_normal(total, dtype=np.float32) * np.float32(10.0 ** int(g.integers(-5, 2)))
+        parts.append(x if in_dt == oracle.F32 else synth.to_bf16_bits(x))
+    want = oracle.reduce(parts, e0, count, out_dt)
+    ies = 4 if in_dt == oracle.F32 else 2
+    oes = 4 if out_dt == oracle.F32 else 2
+    arena = Arena([total * ies] * G)
+    for r in range(G):
+        arena.fill(r, parts[r])
+    out = Arena([count * oes])
+    fcdp.fcdp_reduce_grad_shard(arena.ptrs(), G, e0, count, in_dt, out_dt, out.ptr(0), None)
+    torch.cuda.synchronize()
+    got = out.get(0, np.float32 if out_dt == oracle.F32 else np.uint16)
+    _cmp_reduce(got, want, out_dt)
+    out.check_guards()
+
+
+def test_reduce_special_values_and_order():
+    """Inf, NaN, signed zeros, denormals, cancellation: same bits as the oracle."""
+    G = 6
+    specials = np.array([0x00000000, 0x80000000, 0x00000001, 0x80000001, 0x007FFFFF,
+                         0x00800000, 0x7F7FFFFF, 0xFF7FFFFF, 0x7F800000, 0xFF800000,
+                         0x7FC00000, 0x3F800000, 0xBF800000, 0x4B800000, 0x4B800001,
+                         0x33800000, 0x4CBEBC20, 0xCCBEBC20], dtype=np.uint32)
+    g = synth.rng(0, 77, synth.KIND_MISC)
+    n = 50000
+    parts = [specials[g.integers(0, specials.size, size=n)].view(np.float32).copy() for _ in range(G)]
+    # order-sensitive columns: (2^24 + 1) + 1 and (1e8 + 1) - 1e8
+    parts[0][:2] = [2.0 ** 24, 1e8]
+    parts[1][:2] = [1.0, 1.0]
+    parts[2][:2] = [1.0, -1e8]
+    for r in range(3, G):
+        parts[r][:2] = 0.0
+    # a column of -0.0 must stay -0.0
+    for r in range(G):
+        parts[r][2] = -0.0
+    for out_dt in (oracle.F32, oracle.BF16):
+        with np.errstate(all="ignore"):
+            want = oracle.reduce(parts, 0, n, out_dt)
+        arena = Arena([n * 4] * G)
+        for r in range(G):
+            arena.fill(r, parts[r])
+        out = Arena([n * (4 if out_dt == oracle.F32 else 2)])
+        fcdp.fcdp_reduce_grad_shard(arena.ptrs(), G, 0, n, fcdp.F32, out_dt, out.ptr(0), None)
+        torch.cuda.synchronize()
+        got = out.get(0, np.float32 if out_dt == oracle.F32 else np.uint16)
+        _cmp_reduce(got, want, out_dt)
+        if out_dt == oracle.F32:
+            assert got[0] == np.float32(2.0 ** 24) and got[1] == 0.0
+            assert got.view(np.uint32)[2] == 0x80000000
+
+
+def test_bf16_rounding_all_upper_halves():
+    """G = 1 reduce with bf16 output is the rounding alone: every upper half
+    with 256 lower halves around the rounding edges."""
+    lows = np.concatenate([np.arange(0, 64), np.arange(0x7FE0, 0x8020), np.arange(0xFFC0, 0x10000),
+                           np.arange(0x4000, 0x4040), np.arange(0xBFE0, 0xC000)]).astype(np.uint32)
+    assert lows.size == 256
+    hi = (np.arange(65536, dtype=np.uint32) << 16)
+    u = (hi[:, None] | lows[None, :]).reshape(-1)
+    x = u.view(np.float32)
+    want = oracle.bf16_rne(x)
+    d = to_dev(x)
+    out = torch.empty(x.size * 2, dtype=torch.uint8, device="cuda")
+    fcdp.fcdp_reduce_grad_shard([d], 1, 0, x.size, fcdp.F32, fcdp.BF16, out, None)
+    torch.cuda.synchronize()
+    got = to_host(out, np.uint16)
+    nan = np.isnan(x)
+    assert np.array_equal(got[~nan], want[~nan])
+    # NaN stays NaN with its sign
+    assert np.all((got[nan] & 0x7F80) == 0x7F80) and np.all((got[nan] & 0x7F) != 0)
+    assert np.array_equal(got[nan] >> 15, want[nan] >> 15)
+
+
+def test_reduce_in_place_and_all_ranks():
+    """Every rank's shard in turn; the G shards concatenate to the full sum.
+    Rank r reduces in place into its own partial's slice."""
+    cfg = synth.CONFIGS["gpt2_small_g4"]
+    G, S = 4, 20480 + 64
+    parts = [synth.grad_partial_f32(cfg, 0, r, G * S) for r in range(G)]
+    want = np.concatenate([oracle.reduce(parts, r * S, S, oracle.F32) for r in range(G)])
+    arena = Arena([G * S * 4] * G)
+    for r in range(G):
+        arena.fill(r, parts[r])
+    for r in range(G):
+        fcdp.fcdp_reduce_grad_shard(arena.ptrs(), G, r * S, S, fcdp.F32, fcdp.F32,
+                                    arena.ptr(r) + r * S * 4, None)
+    torch.cuda.synchronize()
+    got = np.concatenate([arena.get(r, np.float32)[r * S:(r + 1) * S] for r in range(G)])
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    arena.check_guards()
+
+
+PACK_CASES = [
+    ("lora_like", [4096, 160, 160, 4096, 160, 160, 9000, 64], [0, 1, 1, 0, 1, 1, 0, 0], 8, 2),
+    ("odd", [1001, 3, 777, 0, 12345, 1], [1, 0, 1, 1, 0, 1], 3, 2),
+    ("all", [500, 700], [1, 1], 4, 2),
+    ("none", [500, 700], [0, 0], 4, 2),
+    ("four_byte", [333, 5000, 77], [0, 1, 1], 2, 4),
+    ("big_runs", [200000, 70000, 300001, 65536], [1, 0, 1, 1], 5, 2),
+]
+
+
+@pytest.mark.parametrize("name,sizes,tr,G,esz", PACK_CASES, ids=[c[0] for c in PACK_CASES])
+def test_pack_unpack_parity(name, sizes, tr, G, esz):
+    dt = np.uint16 if esz == 2 else np.uint32
+    tensors = _rand_tensors(len(sizes) + 50, sizes, dt)
+    flat = oracle.flatten(tensors, G)
+    want_packed = oracle.pack(flat, sizes, tr, G)
+    L = fcdp.fcdp_layout_build(sizes, tr, G, esz)
+    assert L.packed_numel == want_packed.size
+    assert L.trainable_numel == sum(k for k, f in zip(sizes, tr) if f)
+    fa = Arena([flat.size * esz])
+    fa.fill(0, flat)
+    pa = Arena([max(want_packed.size, 0) * esz])
+    fcdp.fcdp_pack_trainable(L, fa.ptr(0), pa.ptr(0), None)
+    torch.cuda.synchronize()
+    assert np.array_equal(pa.get(0, dt), want_packed)
+    pa.check_guards()
+    # unpack new values into a different flat image: frozen bytes untouched
+    newp = _rand_tensors(99, [want_packed.size], dt)[0]
+    base = _rand_tensors(98, [flat.size], dt)[0]
+    want_flat = base.copy()
+    oracle.unpack(newp, want_flat, sizes, tr)
+    pa.fill(0, newp)
+    fb = Arena([flat.size * esz])
+    fb.fill(0, base)
+    fcdp.fcdp_unpack_trainable(L, pa.ptr(0), fb.ptr(0), None)
+    torch.cuda.synchronize()
+    assert np.array_equal(fb.get(0, dt), want_flat)
+    fb.check_guards()
+
+
+def test_unpack_refreshes_mapped_host_cache():
+    """Unpack straight into the device alias of the host cache refreshes H for
+    the trainable parameters only (Alg. 1: only W_t is dirty after a step)."""
+    sizes, tr, G = [4096, 128, 128, 8192, 64], [0, 1, 1, 0, 0], 4
+    tensors = _rand_tensors(5, sizes, np.uint16)
+    flat = oracle.flatten(tensors, G)
+    L = fcdp.fcdp_layout_build(sizes, tr, G, 2)
+    H = fcdp.fcdp_host_cache_alloc(flat.size * 2)
+    H.numpy(np.uint16, flat.size)[:] = flat
+    newp = _rand_tensors(6, [L.packed_numel], np.uint16)[0]
+    want = flat.copy()
+    oracle.unpack(newp, want, sizes, tr)
+    d = to_dev(newp)
+    fcdp.fcdp_unpack_trainable(L, d, H.dev, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(H.numpy(np.uint16, flat.size), want)
+    H.free()
+
+
+def test_double_buffered_backward_sweep():
+    """Several layers with distinct contents through two staging buffers, no
+    host synchronisation between layers: every layer's tensors must be its
+    own (a missing wait would show another layer's bytes)."""
+    sizes = [3 * 1024 * 1024 + 8, 4096, 5 * 1024 * 1024, 1000001]
+    G, esz, nl = 4, 2, 6
+    L = fcdp.fcdp_layout_build(sizes, None, G, esz)
+    Np = L.padded_numel
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    caches, wants = [], []
+    for l in range(nl):
+        tensors = _rand_tensors(700 + l, sizes, np.uint16)
+        flat = oracle.flatten(tensors, G)
+        H = fcdp.fcdp_host_cache_alloc(Np * esz)
+        H.numpy(np.uint16, Np)[:] = flat
+        caches.append(H)
+        wants.append(oracle.materialize_from_flat(flat, sizes))
+    staging = [Arena([Np * esz]), Arena([Np * esz])]
+    outs = [Arena([k * esz for k in sizes]) for _ in range(nl)]
+    for l in range(nl - 1, -1, -1):
+        fcdp.fcdp_materialize_layer(L, fcdp.SRC_HOST_DMA, None, caches[l],
+                                    staging[l % 2].ptr(0), outs[l].ptrs(), False, compute, copy)
+    torch.cuda.synchronize()
+    for l in range(nl):
+        for t in range(len(sizes)):
+            assert np.array_equal(outs[l].get(t, np.uint16), wants[l][t]), (l, t)
+        outs[l].check_guards()
+    for H in caches:
+        H.free()
+
+
+def test_tuning_variants_same_bytes():
+    """Every launch shape gives the same bytes (results do not depend on the
+    block size, the unroll depth, the grid cap or the access hints)."""
+    sizes = [300001, 7, 65537, 131075]
+    G = 3
+    tensors = _rand_tensors(1, sizes, np.uint16)
+    flat = oracle.flatten(tensors, G)
+    shards = oracle.split(flat, G)
+    parts = [synth.grad_partial_f32(synth.CONFIGS["gpt2_small_g4"], 1, r, 200003) for r in range(5)]
+    want_r = oracle.reduce(parts, 3, 200000, oracle.F32)
+    pa = Arena([200003 * 4] * 5)
+    for r in range(5):
+        pa.fill(r, parts[r])
+    defaults = {k: fcdp.fcdp_tuning_get(k) for k in
+                ("copy_chunk_bytes", "copy_block", "copy_unroll", "copy_wg_per_cu", "copy_nt",
+                 "reduce_block", "reduce_unroll", "reduce_nt")}
+    try:
+        for chunk, block, unroll, wg, nt in [(4096, 64, 1, 0, 0), (16384, 128, 2, 2, 1),
+                                             (65536, 256, 4, 0, 1), (262144, 512, 8, 4, 0),
+                                             (1 << 20, 1024, 8, 1, 1)]:
+            fcdp.fcdp_tuning_set("copy_chunk_bytes", chunk)
+            fcdp.fcdp_tuning_set("copy_block", block)
+            fcdp.fcdp_tuning_set("copy_unroll", unroll)
+            fcdp.fcdp_tuning_set("copy_wg_per_cu", wg)
+            fcdp.fcdp_tuning_set("copy_nt", nt)
+            L = fcdp.fcdp_layout_build(sizes, None, G, 2)
+            sh = Arena([L.shard_numel * 2] * G)
+            for r in range(G):
+                sh.fill(r, shards[r])
+            out = Arena([k * 2 for k in sizes])
+            fcdp.fcdp_materialize_layer(L, fcdp.SRC_DEVICE_SHARDS, sh.ptrs(), None, None, out.ptrs())
+            torch.cuda.synchronize()
+            for t in range(len(sizes)):
+                assert np.array_equal(out.get(t, np.uint16), tensors[t])
+            out.check_guards()
+        for block, unroll, nt in [(64, 1, 0), (128, 2, 1), (256, 4, 0), (256, 1, 1)]:
+            fcdp.fcdp_tuning_set("reduce_block", block)
+            fcdp.fcdp_tuning_set("reduce_unroll", unroll)
+            fcdp.fcdp_tuning_set("reduce_nt", nt)
+            out = Arena([200000 * 4])
+            fcdp.fcdp_reduce_grad_shard(pa.ptrs(), 5, 3, 200000, fcdp.F32, fcdp.F32, out.ptr(0))
+            torch.cuda.synchronize()
+            assert np.array_equal(out.get(0, np.float32).view(np.uint32), want_r.view(np.uint32))
+            out.check_guards()
+    finally:
+        for k, v in defaults.items():
+            fcdp.fcdp_tuning_set(k, v)
+
+
+def test_zero_copy_rejects_unpinned_memory():
+    sizes, G = [1024], 2
+    L = fcdp.fcdp_layout_build(sizes, None, G, 2)
+    out = Arena([2048])
+    host = np.zeros(L.padded_numel, dtype=np.uint16)
+    with pytest.raises(fcdp.FcdpError) as e:
+        fcdp.fcdp_materialize_layer(L, fcdp.SRC_HOST_ZEROCOPY, None, host.ctypes.data, None, out.ptrs())
+    assert e.value.name == "FCDP_ENOTPINNED"
+    # the failed call left no sticky error behind: a good call still works
+    sh = Arena([L.shard_numel * 2] * G)
+    fcdp.fcdp_materialize_layer(L, fcdp.SRC_DEVICE_SHARDS, sh.ptrs(), None, None, out.ptrs())
+    torch.cuda.synchronize()
+
+
+def test_probe_copy():
+    n = 3 * 1024 * 1024 + 10
+    x = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")
+    y = torch.zeros_like(x)
+    fcdp.fcdp_probe_copy(y, x, n, None)
+    torch.cuda.synchronize()
+    assert torch.equal(x, y)
