@@ -571,12 +571,6 @@ fcdp_status fcdp_tuning_set(const char *name, int64_t v)
     } else if (n == "reduce_block") {
         if (v < 64 || v > 256 || !pow2(v)) return fail(FCDP_EINVAL, "reduce_block: power of two in 64..256");
         t.reduce_block = v;
-    } else if (n == "reduce_unroll") {
-        if (v != 1 && v != 2 && v != 4) return fail(FCDP_EINVAL, "reduce_unroll: 1, 2 or 4");
-        t.reduce_unroll = v;
-    } else if (n == "reduce_nt") {
-        if (v != 0 && v != 1) return fail(FCDP_EINVAL, "reduce_nt: 0 or 1");
-        t.reduce_nt = v;
     } else {
         return fail(FCDP_EINVAL, "fcdp_tuning_set: unknown knob " + n);
     }
@@ -595,8 +589,6 @@ int64_t fcdp_tuning_get(const char *name)
     if (n == "zc_wg_per_cu") return t.zc_wg_per_cu;
     if (n == "copy_nt") return t.copy_nt;
     if (n == "reduce_block") return t.reduce_block;
-    if (n == "reduce_unroll") return t.reduce_unroll;
-    if (n == "reduce_nt") return t.reduce_nt;
     return -1;
 }
 

@@ -82,8 +82,6 @@ struct Tuning {
     int64_t copy_nt = 1;              // non-temporal loads/stores
     int64_t zc_wg_per_cu = 0;         // same, for the zero-copy fetch
     int64_t reduce_block = 256;
-    int64_t reduce_unroll = 2;        // vectors per thread
-    int64_t reduce_nt = 1;
 };
 Tuning &tuning();
 

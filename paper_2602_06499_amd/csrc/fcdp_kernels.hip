@@ -26,31 +26,49 @@ namespace {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // 16-byte vectors that are only 4- or 2-byte aligned: the compiler picks the
 // widest access the target allows for that alignment.
-typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
-typedef uint32_t u32x4_a2 __attribute__((ext_vector_type(4), aligned(2)));
+typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
+typedef u32x4 u32x4_a2 __attribute__((aligned(2)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x2_a2 __attribute__((ext_vector_type(2), aligned(2)));
+typedef u32x2 u32x2_a2 __attribute__((aligned(2)));
 
 constexpr int kMaxSmall = FCDP_MAX_G;
 
+// All buffer pointers of one launch sit in a single table: entries
+// [0, kMaxSmall) are the short list (shards, or flat/packed), entries from
+// kMaxSmall on are the tensor window.  A piece's indices are turned into
+// table slots by adding src_bias / dst_bias, which the host sets per launch,
+// so the kernel selects its two pointers without any branch on the kind of
+// copy.  (A three-way branch here was compiled to code that left the
+// destination pointer unset on one path.)
 struct CopyArgs {
     const Piece *pieces;
     int64_t n_pieces;
-    int32_t tensor_base;
-    int32_t tensor_side; // 0 dst, 1 src, 2 none
-    char *small_ptrs[kMaxSmall];
-    char *tensor_ptrs[kTensorWindow];
+    int32_t src_bias;
+    int32_t dst_bias;
+    char *ptrs[kMaxSmall + kTensorWindow];
 };
 
-template <typename V, bool NT>
+// Loads 16 bytes from an address that is ALIGN-byte aligned (16, 4 or 2).
+// The under-aligned typedefs are named here directly: a typedef's alignment
+// does not survive being passed as a template type argument.
+template <int ALIGN, bool NT>
 __device__ __forceinline__ u32x4 load16(const char *p)
 {
-    const V *vp = reinterpret_cast<const V *>(p);
-    if constexpr (NT) {
-        V v = __builtin_nontemporal_load(vp);
+    if constexpr (ALIGN >= 16) {
+        const u32x4 *vp = reinterpret_cast<const u32x4 *>(p);
+        if constexpr (NT) return __builtin_nontemporal_load(vp);
+        else return *vp;
+    } else if constexpr (ALIGN >= 4) {
+        const u32x4_a4 *vp = reinterpret_cast<const u32x4_a4 *>(p);
+        u32x4_a4 v;
+        if constexpr (NT) v = __builtin_nontemporal_load(vp);
+        else v = *vp;
         return u32x4{v.x, v.y, v.z, v.w};
     } else {
-        V v = *vp;
+        const u32x4_a2 *vp = reinterpret_cast<const u32x4_a2 *>(p);
+        u32x4_a2 v;
+        if constexpr (NT) v = __builtin_nontemporal_load(vp);
+        else v = *vp;
         return u32x4{v.x, v.y, v.z, v.w};
     }
 }
@@ -65,10 +83,10 @@ __device__ __forceinline__ void store16(char *p, u32x4 v)
         *vp = v;
 }
 
-// Copies nvec 16-byte vectors from s to d; d is 16-byte aligned, s is aligned
-// as V says.  UNROLL independent loads are issued per thread before the
+// Copies nvec 16-byte vectors from s to d; d is 16-byte aligned, s is
+// ALIGN-byte aligned.  UNROLL independent loads are issued per thread before the
 // first store.
-template <typename V, int UNROLL, bool NT>
+template <int ALIGN, int UNROLL, bool NT>
 __device__ __forceinline__ void copy_body(const char *s, char *d, uint32_t nvec,
                                           uint32_t tid, uint32_t nthreads)
 {
@@ -78,7 +96,7 @@ __device__ __forceinline__ void copy_body(const char *s, char *d, uint32_t nvec,
         u32x4 r[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u)
-            r[u] = load16<V, NT>(s + (size_t)(base + u * nthreads + tid) * 16);
+            r[u] = load16<ALIGN, NT>(s + (size_t)(base + u * nthreads + tid) * 16);
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u)
             store16<NT>(d + (size_t)(base + u * nthreads + tid) * 16, r[u]);
@@ -88,7 +106,7 @@ __device__ __forceinline__ void copy_body(const char *s, char *d, uint32_t nvec,
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const uint32_t i = base + u * nthreads + tid;
-            if (i < nvec) r[u] = load16<V, NT>(s + (size_t)i * 16);
+            if (i < nvec) r[u] = load16<ALIGN, NT>(s + (size_t)i * 16);
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
@@ -128,11 +146,11 @@ __device__ __forceinline__ void copy_piece(const char *s, char *d, uint32_t n,
     } else {
         const uint32_t mis = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(s) & 15u);
         if (mis == 0)
-            copy_body<u32x4, UNROLL, NT>(s, d, nvec, tid, nthreads);
+            copy_body<16, UNROLL, NT>(s, d, nvec, tid, nthreads);
         else if ((mis & 3u) == 0)
-            copy_body<u32x4_a4, UNROLL, NT>(s, d, nvec, tid, nthreads);
+            copy_body<4, UNROLL, NT>(s, d, nvec, tid, nthreads);
         else
-            copy_body<u32x4_a2, UNROLL, NT>(s, d, nvec, tid, nthreads);
+            copy_body<2, UNROLL, NT>(s, d, nvec, tid, nthreads);
     }
     // tail: the last n % 16 bytes, 2-byte units
     const uint32_t done = nvec << 4;
@@ -172,20 +190,10 @@ __global__ void copy_pieces(const CopyArgs a)
         const int64_t dst_off = uniform64(p.dst_off);
         const uint32_t nbytes = static_cast<uint32_t>(uniform32(p.nbytes));
         const bool zero = src_idx < 0;
-        const char *s = nullptr;
-        char *d;
-        if (a.tensor_side == 0) {
-            d = a.tensor_ptrs[dst_idx - a.tensor_base];
-            if (!zero) s = a.small_ptrs[src_idx];
-        } else if (a.tensor_side == 1) {
-            d = a.small_ptrs[dst_idx];
-            if (!zero) s = a.tensor_ptrs[src_idx - a.tensor_base];
-        } else {
-            d = a.small_ptrs[1];
-            if (!zero) s = a.small_ptrs[0];
-        }
-        copy_piece<UNROLL, NT>(zero ? nullptr : s + src_off, d + dst_off,
-                               nbytes, zero, tid, nthreads);
+        char *d = a.ptrs[dst_idx + a.dst_bias] + dst_off;
+        // a zero-fill piece reads nothing: point its source at slot 0, unused
+        const char *s = a.ptrs[zero ? 0 : src_idx + a.src_bias] + src_off;
+        copy_piece<UNROLL, NT>(s, d, nbytes, zero, tid, nthreads);
     }
 }
 
@@ -225,10 +233,7 @@ __device__ __forceinline__ void load4(const char *base, int64_t vec, float (&v)[
     if constexpr (IN_F32) {
         const char *p = base + vec * 16;
         u32x4 r;
-        if constexpr (ALIGNED)
-            r = load16<u32x4, NT>(p);
-        else
-            r = load16<u32x4_a4, NT>(p);
+        r = load16<ALIGNED ? 16 : 4, NT>(p);
         v[0] = __uint_as_float(r.x);
         v[1] = __uint_as_float(r.y);
         v[2] = __uint_as_float(r.z);
@@ -268,75 +273,87 @@ __device__ __forceinline__ void store4(char *out, int64_t vec, const float (&a)[
     }
 }
 
-constexpr int kGroup = 8; // partials loaded back to back before the adds
+#ifndef FCDP_REDUCE_UNROLL
+#define FCDP_REDUCE_UNROLL 2 // 4-element vectors per thread
+#endif
+#ifndef FCDP_REDUCE_NT
+#define FCDP_REDUCE_NT 1     // non-temporal loads and stores
+#endif
+constexpr int kGroup = 8;    // partials loaded back to back before their adds
+constexpr int kReduceUnroll = FCDP_REDUCE_UNROLL;
+constexpr bool kReduceNT = FCDP_REDUCE_NT != 0;
 
-// Each thread owns UNROLL groups of four consecutive elements.  The G loads
-// of a group are independent; the adds run strictly in rank order, one
-// binary32 rounding each, so the result does not depend on the launch shape.
-template <bool IN_F32, bool OUT_F32, bool ALIGNED, int UNROLL, bool NT>
+// Adds partials g0 .. g0+K-1 to acc, strictly in that order.  All K*UNROLL
+// loads are issued before the first add.
+template <int K, bool IN_F32, bool ALIGNED, int UNROLL, bool NT>
+__device__ __forceinline__ void add_group(const ReduceArgs &a, int g0,
+                                          const int64_t (&idx)[UNROLL],
+                                          float (&acc)[UNROLL][4])
+{
+    float v[K][UNROLL][4];
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            load4<IN_F32, ALIGNED, NT>(a.p[g0 + k], idx[u], v[k][u]);
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[u][c] = acc[u][c] + v[k][u][c];
+}
+
+// One tile = blockDim.x * UNROLL vectors of four elements starting at b0.
+// GUARD tiles (the last, partial one) clamp their load index to the last
+// vector and skip the stores beyond it, so no load is predicated.
+template <bool GUARD, int REM, bool IN_F32, bool OUT_F32, bool ALIGNED, int UNROLL, bool NT>
+__device__ __forceinline__ void reduce_tile(const ReduceArgs &a, int64_t b0, int64_t nvec)
+{
+    int64_t idx[UNROLL], lidx[UNROLL];
+    float acc[UNROLL][4];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        idx[u] = b0 + static_cast<int64_t>(u) * blockDim.x + threadIdx.x;
+        lidx[u] = GUARD ? (idx[u] < nvec ? idx[u] : nvec - 1) : idx[u];
+        // -0.0f is the identity of IEEE addition for every value including
+        // -0.0f itself, so "acc = -0 + p_0" equals "acc = p_0" bit for bit
+        // and rank 0 needs no special case.
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[u][c] = -0.0f;
+    }
+    const int full = a.G - REM;
+    for (int g = 0; g < full; g += kGroup)
+        add_group<kGroup, IN_F32, ALIGNED, UNROLL, NT>(a, g, lidx, acc);
+    if constexpr (REM > 0)
+        add_group<REM, IN_F32, ALIGNED, UNROLL, NT>(a, full, lidx, acc);
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+        if (!GUARD || idx[u] < nvec) store4<OUT_F32, NT>(a.out, idx[u], acc[u]);
+}
+
+// REM = G mod kGroup is a template parameter, so the rank loop is a counted
+// loop of full groups plus one fixed-size group: no data-dependent branch
+// sits between the loads and the adds.  The adds run strictly in rank
+// order, one binary32 rounding each; the result does not depend on the
+// launch shape.
+template <int REM, bool IN_F32, bool OUT_F32, bool ALIGNED, int UNROLL, bool NT>
 __global__ void __launch_bounds__(256) reduce_ranks(const ReduceArgs a)
 {
     const int64_t nvec = a.count >> 2;
     const int64_t per_block = static_cast<int64_t>(blockDim.x) * UNROLL;
     for (int64_t b0 = static_cast<int64_t>(blockIdx.x) * per_block; b0 < nvec;
          b0 += static_cast<int64_t>(gridDim.x) * per_block) {
-        float acc[UNROLL][4];
-        int64_t idx[UNROLL];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            idx[u] = b0 + static_cast<int64_t>(u) * blockDim.x + threadIdx.x;
-            if (idx[u] < nvec) load4<IN_F32, ALIGNED, NT>(a.p[0], idx[u], acc[u]);
-        }
-        int g = 1;
-        for (; g + kGroup <= a.G; g += kGroup) {
-            float v[kGroup][UNROLL][4];
-#pragma unroll
-            for (int k = 0; k < kGroup; ++k)
-#pragma unroll
-                for (int u = 0; u < UNROLL; ++u)
-                    if (idx[u] < nvec)
-                        load4<IN_F32, ALIGNED, NT>(a.p[g + k], idx[u], v[k][u]);
-#pragma unroll
-            for (int k = 0; k < kGroup; ++k)
-#pragma unroll
-                for (int u = 0; u < UNROLL; ++u)
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) acc[u][c] = acc[u][c] + v[k][u][c];
-        }
-        if (g < a.G) {
-            const int rem = a.G - g; // 1..kGroup-1, wave-uniform
-            float v[kGroup - 1][UNROLL][4];
-#pragma unroll
-            for (int k = 0; k < kGroup - 1; ++k)
-                if (k < rem)
-#pragma unroll
-                    for (int u = 0; u < UNROLL; ++u)
-                        if (idx[u] < nvec)
-                            load4<IN_F32, ALIGNED, NT>(a.p[g + k], idx[u], v[k][u]);
-#pragma unroll
-            for (int k = 0; k < kGroup - 1; ++k)
-                if (k < rem)
-#pragma unroll
-                    for (int u = 0; u < UNROLL; ++u)
-#pragma unroll
-                        for (int c = 0; c < 4; ++c)
-                            acc[u][c] = acc[u][c] + v[k][u][c];
-        }
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u)
-            if (idx[u] < nvec) store4<OUT_F32, NT>(a.out, idx[u], acc[u]);
+        if (b0 + per_block <= nvec)
+            reduce_tile<false, REM, IN_F32, OUT_F32, ALIGNED, UNROLL, NT>(a, b0, nvec);
+        else
+            reduce_tile<true, REM, IN_F32, OUT_F32, ALIGNED, UNROLL, NT>(a, b0, nvec);
     }
     // the last count % 4 elements, one thread each
-    const int64_t done = nvec << 2;
-    const int64_t k = done + threadIdx.x;
+    const int64_t k = (nvec << 2) + threadIdx.x;
     if (blockIdx.x == 0 && k < a.count) {
-        float acc;
-        if constexpr (IN_F32)
-            acc = reinterpret_cast<const float *>(a.p[0])[k];
-        else
-            acc = __uint_as_float(static_cast<uint32_t>(
-                      reinterpret_cast<const uint16_t *>(a.p[0])[k]) << 16);
-        for (int g = 1; g < a.G; ++g) {
+        float acc = -0.0f;
+        for (int g = 0; g < a.G; ++g) {
             float v;
             if constexpr (IN_F32)
                 v = reinterpret_cast<const float *>(a.p[g])[k];
@@ -362,24 +379,27 @@ hipError_t launch_copy_t(const CopyArgs &args, dim3 grid, dim3 block, hipStream_
     return hipGetLastError();
 }
 
-template <bool IN_F32, bool OUT_F32, bool ALIGNED>
-hipError_t launch_reduce_t(const ReduceArgs &args, dim3 grid, dim3 block,
-                           int unroll, bool nt, hipStream_t st)
+template <int REM, bool IN_F32, bool OUT_F32, bool ALIGNED>
+hipError_t launch_reduce_r(const ReduceArgs &args, dim3 grid, dim3 block, hipStream_t st)
 {
-#define FCDP_RED(U, N)                                                         \
-    hipLaunchKernelGGL((reduce_ranks<IN_F32, OUT_F32, ALIGNED, U, N>), grid,   \
-                       block, 0, st, args)
-    if (nt) {
-        if (unroll >= 4) FCDP_RED(4, true);
-        else if (unroll >= 2) FCDP_RED(2, true);
-        else FCDP_RED(1, true);
-    } else {
-        if (unroll >= 4) FCDP_RED(4, false);
-        else if (unroll >= 2) FCDP_RED(2, false);
-        else FCDP_RED(1, false);
-    }
-#undef FCDP_RED
+    hipLaunchKernelGGL((reduce_ranks<REM, IN_F32, OUT_F32, ALIGNED, kReduceUnroll, kReduceNT>),
+                       grid, block, 0, st, args);
     return hipGetLastError();
+}
+
+template <bool IN_F32, bool OUT_F32, bool ALIGNED>
+hipError_t launch_reduce_t(const ReduceArgs &args, dim3 grid, dim3 block, hipStream_t st)
+{
+    switch (args.G % kGroup) {
+    case 0: return launch_reduce_r<0, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st);
+    case 1: return launch_reduce_r<1, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st);
+    case 2: return launch_reduce_r<2, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st);
+    case 3: return launch_reduce_r<3, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st);
+    case 4: return launch_reduce_r<4, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st);
+    case 5: return launch_reduce_r<5, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st);
+    case 6: return launch_reduce_r<6, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st);
+    default: return launch_reduce_r<7, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st);
+    }
 }
 
 } // namespace
@@ -404,15 +424,26 @@ int launch_copy(const CopyLaunch &c, void *stream)
     CopyArgs args;
     args.pieces = c.pieces;
     args.n_pieces = c.n_pieces;
-    args.tensor_base = c.tensor_base;
-    args.tensor_side = c.tensor_side == TensorSide::Dst ? 0
-                       : c.tensor_side == TensorSide::Src ? 1 : 2;
     for (int i = 0; i < kMaxSmall; ++i)
-        args.small_ptrs[i] = i < c.n_small
+        args.ptrs[i] = i < c.n_small
             ? const_cast<char *>(static_cast<const char *>(c.small_ptrs[i])) : nullptr;
     for (int i = 0; i < kTensorWindow; ++i)
-        args.tensor_ptrs[i] = i < c.n_tensor
+        args.ptrs[kMaxSmall + i] = i < c.n_tensor
             ? const_cast<char *>(static_cast<const char *>(c.tensor_ptrs[i])) : nullptr;
+    switch (c.tensor_side) {
+    case TensorSide::Dst: // short list -> tensors
+        args.src_bias = 0;
+        args.dst_bias = kMaxSmall - c.tensor_base;
+        break;
+    case TensorSide::Src: // tensors -> short list
+        args.src_bias = kMaxSmall - c.tensor_base;
+        args.dst_bias = 0;
+        break;
+    default:              // one source buffer (slot 0) -> one destination (slot 1)
+        args.src_bias = 0;
+        args.dst_bias = 1;
+        break;
+    }
     const Tuning &t = tuning();
     int64_t grid = c.n_pieces;
     if (c.wg_per_cu > 0)
@@ -483,26 +514,24 @@ int launch_reduce(const void *const *partials, int32_t G, int64_t elem_offset,
     args.count = count;
     args.G = G;
     const Tuning &t = tuning();
-    const int unroll = static_cast<int>(t.reduce_unroll);
     const int64_t block = t.reduce_block;
     const int64_t nvec = count >> 2;
-    int64_t grid = (nvec + block * unroll - 1) / (block * unroll);
+    int64_t grid = (nvec + block * kReduceUnroll - 1) / (block * kReduceUnroll);
     grid = std::max<int64_t>(1, std::min<int64_t>(grid, 0x7fffffff));
     const dim3 g(static_cast<unsigned>(grid)), b(static_cast<unsigned>(block));
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const bool nt = t.reduce_nt != 0;
     const bool inf = in_dtype == FCDP_F32, outf = out_dtype == FCDP_F32;
     if (inf && outf)
-        return aligned ? launch_reduce_t<true, true, true>(args, g, b, unroll, nt, st)
-                       : launch_reduce_t<true, true, false>(args, g, b, unroll, nt, st);
+        return aligned ? launch_reduce_t<true, true, true>(args, g, b, st)
+                       : launch_reduce_t<true, true, false>(args, g, b, st);
     if (inf && !outf)
-        return aligned ? launch_reduce_t<true, false, true>(args, g, b, unroll, nt, st)
-                       : launch_reduce_t<true, false, false>(args, g, b, unroll, nt, st);
+        return aligned ? launch_reduce_t<true, false, true>(args, g, b, st)
+                       : launch_reduce_t<true, false, false>(args, g, b, st);
     if (!inf && outf)
-        return aligned ? launch_reduce_t<false, true, true>(args, g, b, unroll, nt, st)
-                       : launch_reduce_t<false, true, false>(args, g, b, unroll, nt, st);
-    return aligned ? launch_reduce_t<false, false, true>(args, g, b, unroll, nt, st)
-                   : launch_reduce_t<false, false, false>(args, g, b, unroll, nt, st);
+        return aligned ? launch_reduce_t<false, true, true>(args, g, b, st)
+                       : launch_reduce_t<false, true, false>(args, g, b, st);
+    return aligned ? launch_reduce_t<false, false, true>(args, g, b, st)
+                   : launch_reduce_t<false, false, false>(args, g, b, st);
 }
 
 } // namespace fcdp
