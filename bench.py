@@ -1,0 +1,295 @@
+#!/usr/bin/env python3
+"""Benchmark of the FCDP per-layer hot path on one MI355X.
+
+One step = one pass of the whole path over a Llama-2-7B-shaped stack (32
+layers, G = 8 shards per layer, bf16 parameters, fp32 gradient partials):
+
+  forward, layer 0..L-1   unflatten the G gathered shards into the per-tensor
+                          parameters (kernel, HBM-bound) and store the flat
+                          image to the pinned host cache (D2H DMA, side stream)
+  backward, layer L-1..0  fetch the layer from the host cache (H2D DMA through
+                          two staging buffers, or the zero-copy kernel),
+                          unflatten it, and reduce the G partial gradient
+                          slices into this rank's fp32 shard (kernel)
+  PEFT leg                pack the LoRA parameters out of the flat buffer,
+                          reduce their G packed gradient partials, unpack
+
+Inputs are synthetic and seeded, already resident in HBM / pinned memory when
+the timed region starts.  Prints ONE JSON line (see README).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+LINK_PEAK_GBPS = 63.0           # PCIe Gen5 x16 per direction, 128b/130b
+
+# HBM bytes per unflatten launch measured with rocprofv3 --pmc (FETCH_SIZE,
+# WRITE_SIZE), scaled by the plain-copy calibration; see profiles/.  None
+# until such a run has been recorded for the workload.
+MEASURED_TRAFFIC = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=4)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="llama7b_g8")
+    ap.add_argument("--layers", type=int, default=0, help="0 = the config's layer count")
+    ap.add_argument("--fetch", choices=["dma", "zerocopy"], default="dma")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--cpu-sample-layers", type=int, default=4)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no "
+              "second device); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2602_06499_amd as fcdp
+    from paper_2602_06499_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS[args.config]
+    L = args.layers or cfg.layers
+    G, T = cfg.G, len(cfg.numel)
+    lay = fcdp.fcdp_layout_build(cfg.numel, cfg.trainable, G, 2)
+    lay.prepare()
+    N, Np, S = lay.numel, lay.padded_numel, lay.shard_numel
+    layer_bytes = Np * 2
+
+    def log(msg):
+        print("[bench] " + msg, file=sys.stderr, flush=True)
+
+    log("%s: %d layers, N=%d, G=%d, S=%d, %.1f MB/layer" % (cfg.name, L, N, G, S, layer_bytes / 1e6))
+
+    # ---- inputs, resident before timing --------------------------------
+    gathered = []        # per layer: the G shards as one gather buffer
+    partials = []        # per layer: G fp32 slices of S elements (this rank's slice)
+    for l in range(L):
+        g = synth.torch_device_generator(dev, cfg.config_id, l, synth.KIND_PARAM)
+        w = torch.empty(Np, dtype=torch.bfloat16, device=dev)
+        w.normal_(0.0, 0.02, generator=g)
+        if Np > N:
+            w[N:] = 0
+        gathered.append(w)
+        g = synth.torch_device_generator(dev, cfg.config_id, l, synth.KIND_GRAD)
+        p = torch.empty(G, S, dtype=torch.float32, device=dev)
+        p.normal_(0.0, 1e-3, generator=g)
+        partials.append(p)
+    tensors = [torch.empty(max(k, 1), dtype=torch.bfloat16, device=dev) for k in cfg.numel]
+    staging = [torch.empty(Np, dtype=torch.bfloat16, device=dev) for _ in range(2)]
+    grad_shard = torch.empty(S, dtype=torch.float32, device=dev)
+    t0 = time.time()
+    cache = fcdp.fcdp_host_cache_alloc(layer_bytes * L)
+    log("pinned host cache: %.2f GB in %.1f s" % (layer_bytes * L / 1e9, time.time() - t0))
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    host_mode = fcdp.SRC_HOST_DMA if args.fetch == "dma" else fcdp.SRC_HOST_ZEROCOPY
+    shard_ptrs = [fcdp.pointer_array([w.data_ptr() + r * S * 2 for r in range(G)]) for w in gathered]
+    part_ptrs = [fcdp.pointer_array([p.data_ptr() + r * S * 4 for r in range(G)]) for p in partials]
+    tensor_ptrs = fcdp.pointer_array(tensors)
+    torch.cuda.synchronize()
+
+    def one_step(record):
+        """record: None, or a dict that collects timing events."""
+        ev = torch.cuda.Event
+        if record is not None:
+            e0 = ev(enable_timing=True); e0.record(compute)
+        for l in range(L):
+            if record is not None:
+                a, b = ev(enable_timing=True), ev(enable_timing=True)
+                a.record(compute)
+            fcdp.fcdp_materialize_layer(lay, fcdp.SRC_DEVICE_SHARDS, shard_ptrs[l],
+                                        cache.host + l * layer_bytes, None, tensor_ptrs,
+                                        True, compute, copy)
+            if record is not None:
+                b.record(compute)
+                record["k1"].append((a, b))
+        if record is not None:
+            e1 = ev(enable_timing=True); e1.record(copy)
+        for l in range(L - 1, -1, -1):
+            fcdp.fcdp_materialize_layer(lay, host_mode, None, cache.host + l * layer_bytes,
+                                        staging[l % 2], tensor_ptrs, False, compute, copy)
+            if record is not None:
+                a, b = ev(enable_timing=True), ev(enable_timing=True)
+                a.record(compute)
+            fcdp.fcdp_reduce_grad_shard(part_ptrs[l], G, 0, S, fcdp.F32, fcdp.F32,
+                                        grad_shard, compute)
+            if record is not None:
+                b.record(compute)
+                record["k3"].append((a, b))
+        if record is not None:
+            e2 = ev(enable_timing=True); e2.record(compute)
+            record["sweeps"].append((e0, e1, e2))
+
+    for _ in range(args.warmup):
+        one_step(None)
+    torch.cuda.synchronize()
+    rec = {"k1": [], "k3": [], "sweeps": []}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step(rec)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    k1_ms = sum(a.elapsed_time(b) for a, b in rec["k1"]) / len(rec["k1"])
+    k3_ms = sum(a.elapsed_time(b) for a, b in rec["k3"]) / len(rec["k3"])
+    fwd_ms = sum(e0.elapsed_time(e1) for e0, e1, e2 in rec["sweeps"]) / args.steps
+    bwd_ms = sum(e1.elapsed_time(e2) for e0, e1, e2 in rec["sweeps"]) / args.steps
+    k1_bytes = 4 * N                        # read N*2 + write N*2
+    k3_bytes = G * S * 4 + S * 4            # read G fp32 slices + write one
+    k1_gbps = k1_bytes / (k1_ms * 1e-3) / 1e9
+    k3_gbps = k3_bytes / (k3_ms * 1e-3) / 1e9
+    d2h_gbps = L * layer_bytes / (fwd_ms * 1e-3) / 1e9
+    h2d_gbps = L * layer_bytes / (bwd_ms * 1e-3) / 1e9
+    value = 2 * L * layer_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ---- self-check outside the timed region ---------------------------
+    if not args.no_check:
+        off = lay.offsets
+        flat0 = gathered[0]
+        for t, k in enumerate(cfg.numel):
+            assert torch.equal(tensors[t][:k], flat0[off[t]:off[t] + k]), "materialized tensor mismatch"
+        acc = partials[0][0].clone()
+        for r in range(1, G):
+            acc = acc + partials[0][r]
+        assert torch.equal(acc.view(torch.int32), grad_shard.view(torch.int32)), "gradient shard mismatch"
+        hc = torch.from_numpy(cache.numpy(np.int16, Np, (L - 1) * layer_bytes))
+        assert torch.equal(hc, gathered[L - 1].cpu().view(torch.int16)), "host cache mismatch"
+
+    # ---- host-link probe: one large pinned copy each way ----------------
+    probe_bytes = 2 << 30
+    pin = torch.empty(probe_bytes, dtype=torch.uint8, pin_memory=True)
+    dbuf = torch.empty(probe_bytes, dtype=torch.uint8, device=dev)
+    link = {}
+    for name, (dst, src) in (("h2d", (dbuf, pin)), ("d2h", (pin, dbuf))):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        best = 0.0
+        for _ in range(2):
+            a.record(); dst.copy_(src, non_blocking=True); b.record(); torch.cuda.synchronize()
+            best = max(best, probe_bytes / (a.elapsed_time(b) * 1e-3) / 1e9)
+        link[name] = best
+    del dbuf, pin
+
+    # ---- plain copy reference and the other path variants ---------------
+    def time_kernel(fn, reps=10):
+        fn(); torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(compute)
+        for _ in range(reps):
+            fn()
+        b.record(compute); torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    ref_dst = torch.empty(Np, dtype=torch.bfloat16, device=dev)
+    copy_ms = time_kernel(lambda: fcdp.fcdp_probe_copy(ref_dst, gathered[0], N * 2, compute))
+    del ref_dst
+    zc_ms = time_kernel(lambda: fcdp.fcdp_materialize_layer(
+        lay, fcdp.SRC_HOST_ZEROCOPY, None, cache.host, None, tensors, False, compute, copy), reps=3)
+    dma_ms = time_kernel(lambda: fcdp.fcdp_materialize_layer(
+        lay, fcdp.SRC_HOST_DMA, None, cache.host, staging[0], tensors, False, compute, copy), reps=3)
+    bshard = torch.empty(S, dtype=torch.bfloat16, device=dev)
+    k3b_ms = time_kernel(lambda: fcdp.fcdp_reduce_grad_shard(
+        part_ptrs[0], G, 0, S, fcdp.F32, fcdp.BF16, bshard, compute))
+
+    # ---- PEFT leg: LoRA r16 on q,v of the same stack ---------------------
+    pcfg = synth.CONFIGS["llama7b_lora_g8"]
+    play = fcdp.fcdp_layout_build(pcfg.numel, pcfg.trainable, pcfg.G, 2)
+    play.prepare()
+    pflat = torch.zeros(play.padded_numel, dtype=torch.bfloat16, device=dev)
+    ppacked = torch.zeros(play.packed_numel, dtype=torch.bfloat16, device=dev)
+    pS = play.packed_numel // pcfg.G
+    pgrads = torch.zeros(pcfg.G, pS, dtype=torch.float32, device=dev).normal_(0, 1e-3)
+    pg_ptrs = [pgrads.data_ptr() + r * pS * 4 for r in range(pcfg.G)]
+    pshard = torch.zeros(pS, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    pack_us = 1e3 * time_kernel(lambda: fcdp.fcdp_pack_trainable(play, pflat, ppacked, compute), reps=50)
+    unpack_us = 1e3 * time_kernel(lambda: fcdp.fcdp_unpack_trainable(play, ppacked, pflat, compute), reps=50)
+    pred_us = 1e3 * time_kernel(lambda: fcdp.fcdp_reduce_grad_shard(
+        pg_ptrs, pcfg.G, 0, pS, fcdp.F32, fcdp.F32, pshard, compute), reps=50)
+
+    # ---- CPU oracle on a bounded sample of the same workload -------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.lib()
+        n_s = max(1, min(args.cpu_sample_layers, L))
+        t_cpu = 0.0
+        for l in range(n_s):
+            flat = gathered[l].cpu().view(torch.int16).numpy().view(np.uint16)
+            shards = [flat[r * S:(r + 1) * S] for r in range(G)]
+            parts = [partials[l][r].cpu().numpy() for r in range(G)]
+            t0 = time.perf_counter()
+            tens = oracle.materialize_from_shards(shards, cfg.numel)     # forward
+            H = oracle.cache_store(shards)                               # "H[p] <- p"
+            tens2 = oracle.materialize_from_flat(H, cfg.numel)           # backward
+            red = oracle.reduce(parts, 0, S, oracle.F32)
+            t_cpu += time.perf_counter() - t0
+            if l == 0 and not args.no_check:
+                assert np.array_equal(tens[0], tensors[0][:cfg.numel[0]].cpu().view(torch.int16).numpy().view(np.uint16))
+                assert np.array_equal(red.view(np.uint32), grad_shard.cpu().numpy().view(np.uint32))
+            del tens, tens2, H, red
+        cpu = {"value": round(2 * n_s * layer_bytes / t_cpu / 1e9, 3), "unit": "GB/s",
+               "cores": 1, "kind": "oracle",
+               "sample": "%d of %d layers of %s (materialize from shards, cache store, "
+                         "materialize from cache, fp32 reduce), %.1f s of CPU time, host has %d cores"
+                         % (n_s, L, cfg.name, t_cpu, os.cpu_count())}
+
+    out = {
+        "metric": "layer materialize GB/s (% HBM & host-link peak); grad-shard reduce GB/s",
+        "value": round(value, 3), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 copies, f32 adds", "data": "synthetic",
+        "config": {"workload": "%s: %d layers, hidden 4096, FFN 11008, G=%d shards/layer, "
+                               "forward unflatten + D2H cache store, backward host fetch (%s) + "
+                               "unflatten + fp32 reduce of %d partials"
+                               % (cfg.name, L, G, args.fetch, G),
+                   "layer_bytes": layer_bytes, "fetch": args.fetch},
+        "roofline": {"kernel": "copy_pieces (unflatten, device shards)", "bound": "hbm",
+                     "achieved": round(k1_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(k1_gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": MEASURED_TRAFFIC.get(cfg.name),
+                     "bytes_per_launch": k1_bytes, "avg_launch_ms": round(k1_ms, 4),
+                     "launches_timed": len(rec["k1"])},
+        "roofline_reduce": {"kernel": "reduce_ranks (fp32 in, fp32 out)", "bound": "hbm",
+                            "achieved": round(k3_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                            "frac": round(k3_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                            "bytes_per_launch": k3_bytes, "avg_launch_ms": round(k3_ms, 4),
+                            "bf16_out_gbps": round((G * S * 4 + S * 2) / (k3b_ms * 1e-3) / 1e9, 1)},
+        "host_link": {"peak": LINK_PEAK_GBPS, "unit": "GB/s",
+                      "forward_store_d2h": round(d2h_gbps, 2), "backward_fetch_h2d": round(h2d_gbps, 2),
+                      "frac_d2h": round(d2h_gbps / LINK_PEAK_GBPS, 4), "frac_h2d": round(h2d_gbps / LINK_PEAK_GBPS, 4),
+                      "probe_h2d": round(link["h2d"], 2), "probe_d2h": round(link["d2h"], 2),
+                      "one_layer_dma_fetch_plus_unflatten_ms": round(dma_ms, 3),
+                      "one_layer_zero_copy_ms": round(zc_ms, 3),
+                      "zero_copy_gbps": round(N * 2 / (zc_ms * 1e-3) / 1e9, 2)},
+        "plain_copy_gbps": round(4 * N / (copy_ms * 1e-3) / 1e9, 1),
+        "peft": {"workload": "llama7b_lora_g8 (LoRA r16 on q,v): per layer", "pack_us": round(pack_us, 2),
+                 "unpack_us": round(unpack_us, 2), "reduce_packed_us": round(pred_us, 2),
+                 "trainable_bytes": play.trainable_numel * 2},
+        "cpu_baseline": cpu,
+    }
+    cache.free()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -11,5 +11,5 @@ from .binding import (  # noqa: F401
     fcdp_reduce_grad_shard, fcdp_pack_trainable, fcdp_unpack_trainable,
     fcdp_host_cache_alloc, fcdp_host_cache_free, fcdp_tuning_set,
     fcdp_tuning_get, fcdp_probe_copy, fcdp_last_error, load_library,
-    library_path,
+    library_path, pointer_array,
 )

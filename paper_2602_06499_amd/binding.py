@@ -146,9 +146,16 @@ def _stream(s) -> Optional[int]:
     raise TypeError("cannot take a stream from %r" % type(s))
 
 
+def pointer_array(xs: Sequence):
+    """A reusable C array of pointers (saves the conversion on every call)."""
+    return _ptr_array(list(xs))
+
+
 def _ptr_array(xs: Optional[Sequence]):
     if xs is None:
         return None
+    if isinstance(xs, ctypes.Array):
+        return xs
     arr = (ctypes.c_void_p * max(len(xs), 1))()
     for i, x in enumerate(xs):
         arr[i] = _ptr(x)

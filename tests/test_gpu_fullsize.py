@@ -1,0 +1,86 @@
+"""GPU parity at the benchmark's full layer sizes, in the launch configuration
+bench.py times (default knobs, one contiguous gather buffer per layer, inputs
+drawn on the device from the seeded generator).  One whole layer per shape is
+compared byte for byte with the oracle; the 70B shape also checks the bf16
+shard output."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2602_06499_amd as fcdp
+from paper_2602_06499_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _bits(t):
+    return t.cpu().view(torch.int16).numpy().view(np.uint16)
+
+
+@pytest.mark.parametrize("name,layer", [("llama7b_g8", 3), ("llama7b_lora_g8", 0),
+                                        ("llama13b_g16", 1), ("llama70b_g32", 5)])
+def test_full_layer_materialize_and_reduce(name, layer):
+    cfg = synth.CONFIGS[name]
+    dev = torch.device("cuda:0")
+    G, sizes = cfg.G, list(cfg.numel)
+    L = fcdp.fcdp_layout_build(sizes, cfg.trainable, G, 2)
+    L.prepare()
+    N, Np, S = L.numel, L.padded_numel, L.shard_numel
+    g = synth.torch_device_generator(dev, cfg.config_id, layer, synth.KIND_PARAM)
+    w = torch.empty(Np, dtype=torch.bfloat16, device=dev).normal_(0.0, 0.02, generator=g)
+    tensors = [torch.zeros(max(k, 1), dtype=torch.bfloat16, device=dev) for k in sizes]
+    staging = torch.zeros(Np, dtype=torch.bfloat16, device=dev)
+    H = fcdp.fcdp_host_cache_alloc(Np * 2)
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    shard_ptrs = [w.data_ptr() + r * S * 2 for r in range(G)]
+    flat = _bits(w)
+    shards = [flat[r * S:(r + 1) * S] for r in range(G)]
+    want = oracle.materialize_from_shards(shards, sizes)
+    fcdp.fcdp_materialize_layer(L, fcdp.SRC_DEVICE_SHARDS, shard_ptrs, H, None, tensors, True, compute, copy)
+    torch.cuda.synchronize()
+    for t, k in enumerate(sizes):
+        assert np.array_equal(_bits(tensors[t][:k]), want[t]), (name, "device", t)
+    assert np.array_equal(H.numpy(np.uint16, Np), oracle.cache_store(shards))
+    want2 = oracle.materialize_from_flat(H.numpy(np.uint16, Np), sizes)
+    for mode in (fcdp.SRC_HOST_DMA, fcdp.SRC_HOST_ZEROCOPY):
+        for t in tensors:
+            t.zero_()
+        torch.cuda.synchronize()
+        fcdp.fcdp_materialize_layer(L, mode, None, H, staging, tensors, False, compute, copy)
+        torch.cuda.synchronize()
+        for t, k in enumerate(sizes):
+            assert np.array_equal(_bits(tensors[t][:k]), want2[t]), (name, mode, t)
+    H.free()
+    del w, staging, tensors
+    # gradient shard: G fp32 partial slices of S elements -> fp32 and bf16 shards
+    g = synth.torch_device_generator(dev, cfg.config_id, layer, synth.KIND_GRAD)
+    p = torch.empty(G, S, dtype=torch.float32, device=dev).normal_(0.0, 1e-3, generator=g)
+    ptrs = [p.data_ptr() + r * S * 4 for r in range(G)]
+    out32 = torch.zeros(S, dtype=torch.float32, device=dev)
+    out16 = torch.zeros(S, dtype=torch.bfloat16, device=dev)
+    torch.cuda.synchronize()
+    fcdp.fcdp_reduce_grad_shard(ptrs, G, 0, S, fcdp.F32, fcdp.F32, out32, compute)
+    fcdp.fcdp_reduce_grad_shard(ptrs, G, 0, S, fcdp.F32, fcdp.BF16, out16, compute)
+    torch.cuda.synchronize()
+    parts = [p[r].cpu().numpy() for r in range(G)]
+    assert np.array_equal(out32.cpu().numpy().view(np.uint32),
+                          oracle.reduce(parts, 0, S, oracle.F32).view(np.uint32))
+    assert np.array_equal(_bits(out16), oracle.reduce(parts, 0, S, oracle.BF16))
+    if sum(cfg.trainable) != len(sizes):
+        # PEFT shape: pack, then unpack updated values; frozen bytes untouched
+        d_flat = torch.from_numpy(flat.view(np.int16).copy()).to(dev)
+        packed = torch.zeros(L.packed_numel, dtype=torch.int16, device=dev)
+        fcdp.fcdp_pack_trainable(L, d_flat, packed, compute)
+        torch.cuda.synchronize()
+        assert np.array_equal(packed.cpu().numpy().view(np.uint16),
+                              oracle.pack(flat, sizes, cfg.trainable, G))
+        newp = synth.rng(0, 5, synth.KIND_MISC).integers(0, 65536, size=L.packed_numel, dtype=np.uint16)
+        wantf = flat.copy()
+        oracle.unpack(newp, wantf, sizes, cfg.trainable)
+        packed.copy_(torch.from_numpy(newp.view(np.int16).copy()))
+        torch.cuda.synchronize()
+        fcdp.fcdp_unpack_trainable(L, packed, d_flat, compute)
+        torch.cuda.synchronize()
+        assert np.array_equal(d_flat.cpu().numpy().view(np.uint16), wantf)
