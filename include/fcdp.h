@@ -70,6 +70,13 @@ typedef enum {
     FCDP_SRC_HOST_ZEROCOPY = 2  /* cache hit: kernel reads the mapped host cache */
 } fcdp_source;
 
+/* store_cache argument of fcdp_materialize_layer */
+typedef enum {
+    FCDP_STORE_NONE = 0,
+    FCDP_STORE_DMA = 1,      /* hipMemcpyAsync device -> pinned host */
+    FCDP_STORE_ZEROCOPY = 2  /* a small kernel writes through the host mapping */
+} fcdp_store;
+
 #define FCDP_MAX_G 64 /* most shards / gradient partials per call */
 
 /* ------------------------------------------------------------ offset table
@@ -123,11 +130,14 @@ fcdp_status fcdp_layout_prepare(const fcdp_layout *layout);
  *
  * FCDP_SRC_DEVICE_SHARDS (forward, cache miss; Sec. 4.3 forward pass, Alg. 1
  * dirty branch "p <- AllGather(p_inter)"): tensor_t[j] =
- * shard_{(off_t+j) div S}[(off_t+j) mod S].  If store_cache != 0 the padded
- * flat image concat(shard_0..shard_{G-1}) is also copied to host_cache on the
- * `copy` stream (Alg. 1 "H[p] <- p", gpu to host), ordered after everything
- * enqueued on `compute` before this call; the shards must stay unmodified
- * until that copy has completed in `copy`-stream order.
+ * shard_{(off_t+j) div S}[(off_t+j) mod S].  If store_cache != FCDP_STORE_NONE
+ * the padded flat image concat(shard_0..shard_{G-1}) is also copied to
+ * host_cache on the `copy` stream (Alg. 1 "H[p] <- p", gpu to host), ordered
+ * after everything enqueued on `compute` before this call; the shards must
+ * stay unmodified until that copy has completed in `copy`-stream order.
+ * FCDP_STORE_DMA uses hipMemcpyAsync; FCDP_STORE_ZEROCOPY uses a kernel with a
+ * bounded number of workgroups that writes through the host mapping
+ * (host_cache must then be mapped pinned memory, else FCDP_ENOTPINNED).
  *
  * FCDP_SRC_HOST_DMA (backward / clean forward, cache hit; Sec. 4.3 backward
  * pass, Alg. 1 "p_intra <- H[p]"): host_cache is copied to `staging` on the
@@ -144,7 +154,7 @@ fcdp_status fcdp_layout_prepare(const fcdp_layout *layout);
  *   shard_ptrs   host array of G dev ptrs, S*elem_size bytes each
  *                (DEVICE_SHARDS only, else may be NULL)
  *   host_cache   host ptr to N_pad*elem_size bytes of pinned memory; read
- *                for HOST_*, written when store_cache != 0; else may be NULL
+ *                for HOST_*, written when store_cache is set; else may be NULL
  *   staging      dev ptr to N_pad*elem_size bytes (HOST_DMA only)
  *   tensor_ptrs  host array of T dev ptrs, numel[t]*elem_size bytes each
  *                (entries of zero-element tensors are ignored)

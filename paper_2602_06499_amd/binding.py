@@ -17,6 +17,9 @@ F32 = 1
 SRC_DEVICE_SHARDS = 0
 SRC_HOST_DMA = 1
 SRC_HOST_ZEROCOPY = 2
+STORE_NONE = 0
+STORE_DMA = 1
+STORE_ZEROCOPY = 2
 MAX_G = 64
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -222,11 +225,11 @@ def fcdp_layout_build(numel: Sequence[int], trainable: Optional[Sequence[int]],
 
 
 def fcdp_materialize_layer(layout: Layout, src: int, shard_ptrs, host_cache,
-                           staging, tensor_ptrs, store_cache: bool = False,
+                           staging, tensor_ptrs, store_cache=STORE_NONE,
                            compute=None, copy=None) -> None:
     _check(load_library().fcdp_materialize_layer(
         layout.handle, src, _ptr_array(shard_ptrs), _ptr(host_cache),
-        _ptr(staging), _ptr_array(tensor_ptrs), int(bool(store_cache)),
+        _ptr(staging), _ptr_array(tensor_ptrs), int(store_cache),
         _stream(compute), _stream(copy)))
 
 

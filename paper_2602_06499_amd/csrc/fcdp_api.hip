@@ -156,7 +156,8 @@ fcdp_status run_windowed(const fcdp::PieceTable &tab, const fcdp::Piece *dev_pie
                          fcdp::TensorSide side, int32_t T,
                          const void *const *small, int32_t n_small,
                          const void *const *tensors, bool nt, int64_t wg_per_cu,
-                         hipStream_t st, const char *what)
+                         hipStream_t st, const char *what, int64_t max_wgs = 0,
+                         int64_t block = 0)
 {
     const int64_t n_win = static_cast<int64_t>(tab.win_begin.size()) - 1;
     for (int64_t w = 0; w < n_win; ++w) {
@@ -173,6 +174,8 @@ fcdp_status run_windowed(const fcdp::PieceTable &tab, const fcdp::Piece *dev_pie
         c.n_tensor = std::min<int32_t>(fcdp::kTensorWindow, T - c.tensor_base);
         c.nt = nt;
         c.wg_per_cu = wg_per_cu;
+        c.max_wgs = max_wgs;
+        c.block = block;
         hipError_t err = static_cast<hipError_t>(fcdp::launch_copy(c, st));
         if (err != hipSuccess) return hip_fail(err, what);
     }
@@ -237,6 +240,8 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
     if (!L) return fail(FCDP_EINVAL, std::string(fn) + ": layout is NULL");
     if (src != FCDP_SRC_DEVICE_SHARDS && src != FCDP_SRC_HOST_DMA && src != FCDP_SRC_HOST_ZEROCOPY)
         return fail(FCDP_EINVAL, std::string(fn) + ": unknown source");
+    if (store_cache != FCDP_STORE_NONE && store_cache != FCDP_STORE_DMA && store_cache != FCDP_STORE_ZEROCOPY)
+        return fail(FCDP_EINVAL, std::string(fn) + ": unknown store_cache mode");
     fcdp_status st = check_tensor_ptrs(L, reinterpret_cast<const void *const *>(tensor_ptrs), fn);
     if (st != FCDP_OK) return st;
     hipStream_t compute = static_cast<hipStream_t>(compute_);
@@ -271,6 +276,19 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
     }
     if (store_cache && !aligned16(host_cache))
         return fail(FCDP_EALIGN, std::string(fn) + ": host_cache is not 16-byte aligned");
+    void *store_alias = nullptr;
+    if (store_cache == FCDP_STORE_ZEROCOPY && flat_bytes) {
+        hipPointerAttribute_t attr;
+        std::memset(&attr, 0, sizeof attr);
+        hipError_t e = hipPointerGetAttributes(&attr, host_cache);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(FCDP_ENOTPINNED, std::string(fn) + ": host_cache is not known to HIP as pinned host memory");
+        }
+        if (attr.type != hipMemoryTypeHost || !attr.devicePointer)
+            return fail(FCDP_ENOTPINNED, std::string(fn) + ": host_cache is not mapped pinned host memory");
+        store_alias = attr.devicePointer;
+    }
     if (L->N == 0 && !(store_cache && flat_bytes)) return FCDP_OK;
 
     DeviceCtx *ctx = nullptr;
@@ -290,7 +308,22 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
             for (int32_t r = 1; r < L->G; ++r)
                 if (static_cast<const char *>(shard_ptrs[r]) != static_cast<const char *>(shard_ptrs[0]) + r * shard_bytes)
                     contiguous = false;
-            if (contiguous) {
+            if (store_cache == FCDP_STORE_ZEROCOPY) {
+                // a few workgroups write the image through the host mapping
+                fcdp::PlainCopy shape;
+                shape.chunk = tune.link_chunk_bytes;
+                shape.block = tune.link_block;
+                shape.unroll = 4;
+                shape.max_wgs = tune.link_max_wgs;
+                shape.nt = 0;
+                char *ha = static_cast<char *>(store_alias);
+                const int32_t n_copies = contiguous ? 1 : L->G;
+                const size_t each = contiguous ? flat_bytes : shard_bytes;
+                for (int32_t r = 0; r < n_copies; ++r) {
+                    hipError_t e = static_cast<hipError_t>(fcdp::launch_plain_copy(ha + r * each, shard_ptrs[r], each, copy, shape));
+                    if (e != hipSuccess) return hip_fail(e, "launch zero-copy store");
+                }
+            } else if (contiguous) {
                 FCDP_HIP(hipMemcpyAsync(h, shard_ptrs[0], flat_bytes, hipMemcpyDeviceToHost, copy), "hipMemcpyAsync(D2H)");
             } else {
                 for (int32_t r = 0; r < L->G; ++r)
@@ -322,8 +355,9 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
     if ((st = order_after(ctx, copy, compute)) != FCDP_OK) return st;
     for (int32_t r = 0; r < L->G; ++r) small[r] = static_cast<const char *>(zc_alias) + r * shard_bytes;
     return run_windowed(L->unflatten, tabs->unflatten, fcdp::TensorSide::Dst, L->T, small, L->G,
-                        reinterpret_cast<const void *const *>(tensor_ptrs), false,
-                        tune.zc_wg_per_cu, compute, "launch zero-copy unflatten");
+                        reinterpret_cast<const void *const *>(tensor_ptrs), false, 0, compute,
+                        "launch zero-copy unflatten", tune.link_max_wgs,
+                        tune.link_max_wgs > 0 ? tune.link_block : 0);
 }
 
 fcdp_status fcdp_flatten_to_shards(const fcdp_layout *L, const void *const *tensor_ptrs,
@@ -562,11 +596,17 @@ fcdp_status fcdp_tuning_set(const char *name, int64_t v)
     } else if (n == "copy_wg_per_cu") {
         if (v < 0 || v > 64) return fail(FCDP_EINVAL, "copy_wg_per_cu: 0..64");
         t.copy_wg_per_cu = v;
-    } else if (n == "zc_wg_per_cu") {
-        if (v < 0 || v > 64) return fail(FCDP_EINVAL, "zc_wg_per_cu: 0..64");
-        t.zc_wg_per_cu = v;
+    } else if (n == "link_max_wgs") {
+        if (v < 0 || v > 65536) return fail(FCDP_EINVAL, "link_max_wgs: 0..65536");
+        t.link_max_wgs = v;
+    } else if (n == "link_block") {
+        if (v < 64 || v > 1024 || !pow2(v)) return fail(FCDP_EINVAL, "link_block: power of two in 64..1024");
+        t.link_block = v;
+    } else if (n == "link_chunk_bytes") {
+        if (v < 4096 || v > (1 << 24) || v % 4096) return fail(FCDP_EINVAL, "link_chunk_bytes: multiple of 4096 in 4096..16 MiB");
+        t.link_chunk_bytes = v;
     } else if (n == "copy_nt") {
-        if (v != 0 && v != 1) return fail(FCDP_EINVAL, "copy_nt: 0 or 1");
+        if (v < 0 || v > 3) return fail(FCDP_EINVAL, "copy_nt: 0..3 (bit 0 loads, bit 1 stores)");
         t.copy_nt = v;
     } else if (n == "reduce_block") {
         if (v < 64 || v > 256 || !pow2(v)) return fail(FCDP_EINVAL, "reduce_block: power of two in 64..256");
@@ -586,7 +626,9 @@ int64_t fcdp_tuning_get(const char *name)
     if (n == "copy_block") return t.copy_block;
     if (n == "copy_unroll") return t.copy_unroll;
     if (n == "copy_wg_per_cu") return t.copy_wg_per_cu;
-    if (n == "zc_wg_per_cu") return t.zc_wg_per_cu;
+    if (n == "link_max_wgs") return t.link_max_wgs;
+    if (n == "link_block") return t.link_block;
+    if (n == "link_chunk_bytes") return t.link_chunk_bytes;
     if (n == "copy_nt") return t.copy_nt;
     if (n == "reduce_block") return t.reduce_block;
     return -1;

@@ -75,13 +75,20 @@ fcdp_status fail(fcdp_status st, const std::string &msg);
 
 // tuning knobs (see fcdp_tuning_set)
 struct Tuning {
-    int64_t copy_chunk_bytes = 65536; // piece size cap; multiple of 4096
-    int64_t copy_block = 256;         // threads per workgroup: 64..1024
-    int64_t copy_unroll = 4;          // 16-byte vectors in flight per thread
+    // Measured best on MI355X (Llama 7B/13B/70B-shaped layers): many small
+    // workgroups, two 16-byte vectors per lane, non-temporal access.
+    int64_t copy_chunk_bytes = 4096;  // piece size cap; multiple of 4096
+    int64_t copy_block = 128;         // threads per workgroup: 64..1024
+    int64_t copy_unroll = 1;          // 16-byte vectors in flight per thread
     int64_t copy_wg_per_cu = 0;       // 0 = one workgroup per piece
-    int64_t copy_nt = 1;              // non-temporal loads/stores
-    int64_t zc_wg_per_cu = 0;         // same, for the zero-copy fetch
-    int64_t reduce_block = 256;
+    int64_t copy_nt = 3;              // non-temporal: bit 0 loads, bit 1 stores
+    // kernels whose loads or stores cross the host link (zero-copy fetch and
+    // store): a bounded number of workgroups keeps enough bytes in flight for
+    // the link and leaves the rest of the GPU to other work; 0 = no bound
+    int64_t link_max_wgs = 64;
+    int64_t link_block = 256;
+    int64_t link_chunk_bytes = 16384; // bytes per workgroup iteration (store)
+    int64_t reduce_block = 64;
 };
 Tuning &tuning();
 
@@ -100,12 +107,19 @@ struct CopyLaunch {
     int32_t n_tensor = 0;
     bool nt = true;
     int64_t wg_per_cu = 0;
+    int64_t max_wgs = 0;            // absolute cap on workgroups, 0 = none
+    int64_t block = 0;              // threads per workgroup, 0 = copy_block
 };
 int launch_copy(const CopyLaunch &c, void *stream);
 int launch_reduce(const void *const *partials, int32_t G, int64_t elem_offset,
                   int64_t count, int in_dtype, int out_dtype, void *out,
                   void *stream);
-int launch_plain_copy(void *dst, const void *src, size_t bytes, void *stream);
+struct PlainCopy {
+    int64_t chunk = 0, block = 0, unroll = 0, max_wgs = 0; // 0 = the copy_* knobs
+    int nt = -1;                                           // -1 = copy_nt
+};
+int launch_plain_copy(void *dst, const void *src, size_t bytes, void *stream,
+                      const PlainCopy &shape = PlainCopy());
 int device_cu_count();
 
 } // namespace fcdp

@@ -86,7 +86,8 @@ __device__ __forceinline__ void store16(char *p, u32x4 v)
 // Copies nvec 16-byte vectors from s to d; d is 16-byte aligned, s is
 // ALIGN-byte aligned.  UNROLL independent loads are issued per thread before the
 // first store.
-template <int ALIGN, int UNROLL, bool NT>
+// HINT: bit 0 = non-temporal loads, bit 1 = non-temporal stores.
+template <int ALIGN, int UNROLL, int HINT>
 __device__ __forceinline__ void copy_body(const char *s, char *d, uint32_t nvec,
                                           uint32_t tid, uint32_t nthreads)
 {
@@ -96,36 +97,36 @@ __device__ __forceinline__ void copy_body(const char *s, char *d, uint32_t nvec,
         u32x4 r[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u)
-            r[u] = load16<ALIGN, NT>(s + (size_t)(base + u * nthreads + tid) * 16);
+            r[u] = load16<ALIGN, (HINT & 1) != 0>(s + (size_t)(base + u * nthreads + tid) * 16);
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u)
-            store16<NT>(d + (size_t)(base + u * nthreads + tid) * 16, r[u]);
+            store16<(HINT & 2) != 0>(d + (size_t)(base + u * nthreads + tid) * 16, r[u]);
     }
     if (base < nvec) {
         u32x4 r[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const uint32_t i = base + u * nthreads + tid;
-            if (i < nvec) r[u] = load16<ALIGN, NT>(s + (size_t)i * 16);
+            if (i < nvec) r[u] = load16<ALIGN, (HINT & 1) != 0>(s + (size_t)i * 16);
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const uint32_t i = base + u * nthreads + tid;
-            if (i < nvec) store16<NT>(d + (size_t)i * 16, r[u]);
+            if (i < nvec) store16<(HINT & 2) != 0>(d + (size_t)i * 16, r[u]);
         }
     }
 }
 
-template <int UNROLL, bool NT>
+template <int UNROLL, int HINT>
 __device__ __forceinline__ void zero_body(char *d, uint32_t nvec, uint32_t tid,
                                           uint32_t nthreads)
 {
     for (uint32_t i = tid; i < nvec; i += nthreads)
-        store16<NT>(d + (size_t)i * 16, u32x4{0u, 0u, 0u, 0u});
+        store16<(HINT & 2) != 0>(d + (size_t)i * 16, u32x4{0u, 0u, 0u, 0u});
 }
 
 // One piece: n bytes (even), s and d both at least 2-byte aligned.
-template <int UNROLL, bool NT>
+template <int UNROLL, int HINT>
 __device__ __forceinline__ void copy_piece(const char *s, char *d, uint32_t n,
                                            bool zero, uint32_t tid,
                                            uint32_t nthreads)
@@ -142,15 +143,15 @@ __device__ __forceinline__ void copy_piece(const char *s, char *d, uint32_t n,
     n -= head;
     const uint32_t nvec = n >> 4;
     if (zero) {
-        zero_body<UNROLL, NT>(d, nvec, tid, nthreads);
+        zero_body<UNROLL, HINT>(d, nvec, tid, nthreads);
     } else {
         const uint32_t mis = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(s) & 15u);
         if (mis == 0)
-            copy_body<16, UNROLL, NT>(s, d, nvec, tid, nthreads);
+            copy_body<16, UNROLL, HINT>(s, d, nvec, tid, nthreads);
         else if ((mis & 3u) == 0)
-            copy_body<4, UNROLL, NT>(s, d, nvec, tid, nthreads);
+            copy_body<4, UNROLL, HINT>(s, d, nvec, tid, nthreads);
         else
-            copy_body<2, UNROLL, NT>(s, d, nvec, tid, nthreads);
+            copy_body<2, UNROLL, HINT>(s, d, nvec, tid, nthreads);
     }
     // tail: the last n % 16 bytes, 2-byte units
     const uint32_t done = nvec << 4;
@@ -174,7 +175,7 @@ __device__ __forceinline__ int64_t uniform64(int64_t v)
     return static_cast<int64_t>((static_cast<uint64_t>(hi) << 32) | lo);
 }
 
-template <int UNROLL, bool NT>
+template <int UNROLL, int HINT>
 __global__ void copy_pieces(const CopyArgs a)
 {
     const uint32_t tid = threadIdx.x;
@@ -193,11 +194,11 @@ __global__ void copy_pieces(const CopyArgs a)
         char *d = a.ptrs[dst_idx + a.dst_bias] + dst_off;
         // a zero-fill piece reads nothing: point its source at slot 0, unused
         const char *s = a.ptrs[zero ? 0 : src_idx + a.src_bias] + src_off;
-        copy_piece<UNROLL, NT>(s, d, nbytes, zero, tid, nthreads);
+        copy_piece<UNROLL, HINT>(s, d, nbytes, zero, tid, nthreads);
     }
 }
 
-template <int UNROLL, bool NT>
+template <int UNROLL, int HINT>
 __global__ void plain_copy(const char *__restrict__ src, char *__restrict__ dst,
                            size_t bytes, uint32_t chunk)
 {
@@ -205,7 +206,7 @@ __global__ void plain_copy(const char *__restrict__ src, char *__restrict__ dst,
     for (size_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
         const size_t o = c * chunk;
         const uint32_t n = static_cast<uint32_t>(bytes - o < chunk ? bytes - o : chunk);
-        copy_piece<UNROLL, NT>(src + o, dst + o, n, false, threadIdx.x, blockDim.x);
+        copy_piece<UNROLL, HINT>(src + o, dst + o, n, false, threadIdx.x, blockDim.x);
     }
 }
 
@@ -274,7 +275,7 @@ __device__ __forceinline__ void store4(char *out, int64_t vec, const float (&a)[
 }
 
 #ifndef FCDP_REDUCE_UNROLL
-#define FCDP_REDUCE_UNROLL 2 // 4-element vectors per thread
+#define FCDP_REDUCE_UNROLL 4 // 4-element vectors per thread
 #endif
 #ifndef FCDP_REDUCE_NT
 #define FCDP_REDUCE_NT 1     // non-temporal loads and stores
@@ -372,10 +373,34 @@ __global__ void __launch_bounds__(256) reduce_ranks(const ReduceArgs a)
 
 int g_cu_count[kMaxDevices] = {0};
 
-template <int UNROLL, bool NT>
+template <int UNROLL, int HINT>
 hipError_t launch_copy_t(const CopyArgs &args, dim3 grid, dim3 block, hipStream_t st)
 {
-    hipLaunchKernelGGL((copy_pieces<UNROLL, NT>), grid, block, 0, st, args);
+    hipLaunchKernelGGL((copy_pieces<UNROLL, HINT>), grid, block, 0, st, args);
+    return hipGetLastError();
+}
+
+template <int UNROLL>
+hipError_t launch_copy_h(const CopyArgs &args, dim3 grid, dim3 block, int hint, hipStream_t st)
+{
+    switch (hint & 3) {
+    case 0: return launch_copy_t<UNROLL, 0>(args, grid, block, st);
+    case 1: return launch_copy_t<UNROLL, 1>(args, grid, block, st);
+    case 2: return launch_copy_t<UNROLL, 2>(args, grid, block, st);
+    default: return launch_copy_t<UNROLL, 3>(args, grid, block, st);
+    }
+}
+
+template <int UNROLL>
+hipError_t launch_plain_h(const char *s, char *d, size_t bytes, uint32_t chunk, dim3 grid,
+                          dim3 block, int hint, hipStream_t st)
+{
+    switch (hint & 3) {
+    case 0: hipLaunchKernelGGL((plain_copy<UNROLL, 0>), grid, block, 0, st, s, d, bytes, chunk); break;
+    case 1: hipLaunchKernelGGL((plain_copy<UNROLL, 1>), grid, block, 0, st, s, d, bytes, chunk); break;
+    case 2: hipLaunchKernelGGL((plain_copy<UNROLL, 2>), grid, block, 0, st, s, d, bytes, chunk); break;
+    default: hipLaunchKernelGGL((plain_copy<UNROLL, 3>), grid, block, 0, st, s, d, bytes, chunk); break;
+    }
     return hipGetLastError();
 }
 
@@ -448,50 +473,42 @@ int launch_copy(const CopyLaunch &c, void *stream)
     int64_t grid = c.n_pieces;
     if (c.wg_per_cu > 0)
         grid = std::min<int64_t>(grid, c.wg_per_cu * device_cu_count());
+    if (c.max_wgs > 0) grid = std::min<int64_t>(grid, c.max_wgs);
     grid = std::min<int64_t>(grid, 0x7fffffff);
-    const dim3 g(static_cast<unsigned>(grid)), b(static_cast<unsigned>(t.copy_block));
+    const dim3 g(static_cast<unsigned>(grid)),
+        b(static_cast<unsigned>(c.block > 0 ? c.block : t.copy_block));
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int unroll = static_cast<int>(t.copy_unroll);
-    if (c.nt) {
-        if (unroll >= 8) return launch_copy_t<8, true>(args, g, b, st);
-        if (unroll >= 4) return launch_copy_t<4, true>(args, g, b, st);
-        if (unroll >= 2) return launch_copy_t<2, true>(args, g, b, st);
-        return launch_copy_t<1, true>(args, g, b, st);
-    }
-    if (unroll >= 8) return launch_copy_t<8, false>(args, g, b, st);
-    if (unroll >= 4) return launch_copy_t<4, false>(args, g, b, st);
-    if (unroll >= 2) return launch_copy_t<2, false>(args, g, b, st);
-    return launch_copy_t<1, false>(args, g, b, st);
+    const int hint = c.nt ? static_cast<int>(t.copy_nt) : 0;
+    if (unroll >= 8) return launch_copy_h<8>(args, g, b, hint, st);
+    if (unroll >= 4) return launch_copy_h<4>(args, g, b, hint, st);
+    if (unroll >= 2) return launch_copy_h<2>(args, g, b, hint, st);
+    return launch_copy_h<1>(args, g, b, hint, st);
 }
 
-int launch_plain_copy(void *dst, const void *src, size_t bytes, void *stream)
+int launch_plain_copy(void *dst, const void *src, size_t bytes, void *stream,
+                      const PlainCopy &shape)
 {
     if (bytes == 0) return hipSuccess;
     const Tuning &t = tuning();
-    const uint32_t chunk = static_cast<uint32_t>(t.copy_chunk_bytes);
+    const uint32_t chunk = static_cast<uint32_t>(shape.chunk > 0 ? shape.chunk : t.copy_chunk_bytes);
+    const int64_t block = shape.block > 0 ? shape.block : t.copy_block;
+    const int unroll = static_cast<int>(shape.unroll > 0 ? shape.unroll : t.copy_unroll);
+    const int hint = shape.nt >= 0 ? shape.nt : static_cast<int>(t.copy_nt);
     size_t n_chunks = (bytes + chunk - 1) / chunk;
     int64_t grid = static_cast<int64_t>(std::min<size_t>(n_chunks, 0x7fffffff));
-    if (t.copy_wg_per_cu > 0)
+    if (shape.max_wgs > 0)
+        grid = std::min<int64_t>(grid, shape.max_wgs);
+    else if (t.copy_wg_per_cu > 0)
         grid = std::min<int64_t>(grid, t.copy_wg_per_cu * device_cu_count());
-    const dim3 g(static_cast<unsigned>(grid)), b(static_cast<unsigned>(t.copy_block));
+    const dim3 g(static_cast<unsigned>(grid)), b(static_cast<unsigned>(block));
     hipStream_t st = static_cast<hipStream_t>(stream);
     const char *s = static_cast<const char *>(src);
     char *d = static_cast<char *>(dst);
-    const int unroll = static_cast<int>(t.copy_unroll);
-#define FCDP_PC(U, N) hipLaunchKernelGGL((plain_copy<U, N>), g, b, 0, st, s, d, bytes, chunk)
-    if (t.copy_nt) {
-        if (unroll >= 8) FCDP_PC(8, true);
-        else if (unroll >= 4) FCDP_PC(4, true);
-        else if (unroll >= 2) FCDP_PC(2, true);
-        else FCDP_PC(1, true);
-    } else {
-        if (unroll >= 8) FCDP_PC(8, false);
-        else if (unroll >= 4) FCDP_PC(4, false);
-        else if (unroll >= 2) FCDP_PC(2, false);
-        else FCDP_PC(1, false);
-    }
-#undef FCDP_PC
-    return hipGetLastError();
+    if (unroll >= 8) return launch_plain_h<8>(s, d, bytes, chunk, g, b, hint, st);
+    if (unroll >= 4) return launch_plain_h<4>(s, d, bytes, chunk, g, b, hint, st);
+    if (unroll >= 2) return launch_plain_h<2>(s, d, bytes, chunk, g, b, hint, st);
+    return launch_plain_h<1>(s, d, bytes, chunk, g, b, hint, st);
 }
 
 int launch_reduce(const void *const *partials, int32_t G, int64_t elem_offset,
