@@ -110,7 +110,7 @@ def main():
     torch.cuda.synchronize()
 
     def one_step(record):
-        """record: None, or a dict that collects timing events."""
+        """record: None, or a list that collects the sweep events."""
         ev = torch.cuda.Event
         if record is not None:
             e0 = ev(enable_timing=True); e0.record(compute)
@@ -119,42 +119,39 @@ def main():
                                         cache.host + l * layer_bytes, None, tensor_ptrs,
                                         store_mode, compute, copy)
         if record is not None:
-            # the forward sweep's L unflatten launches run back to back on the
-            # compute stream (the cache stores go to the copy stream), so one
-            # event pair around them times L launches
-            ek = ev(enable_timing=True); ek.record(compute)
-            record["k1"].append((e0, ek))
             e1 = ev(enable_timing=True); e1.record(copy)
         for l in range(L - 1, -1, -1):
             fcdp.fcdp_materialize_layer(lay, host_mode, None, cache.host + l * layer_bytes,
                                         staging[l % 2], tensor_ptrs, False, compute, copy)
-            if record is not None:
-                a, b = ev(enable_timing=True), ev(enable_timing=True)
-                a.record(compute)
             fcdp.fcdp_reduce_grad_shard(part_ptrs[l], G, 0, S, fcdp.F32, fcdp.F32,
                                         grad_shard, compute)
-            if record is not None:
-                b.record(compute)
-                record["k3"].append((a, b))
         if record is not None:
             e2 = ev(enable_timing=True); e2.record(compute)
-            record["sweeps"].append((e0, e1, e2))
+            record.append((e0, e1, e2))
 
     for _ in range(args.warmup):
         one_step(None)
     torch.cuda.synchronize()
-    rec = {"k1": [], "k3": [], "sweeps": []}
+    # every kernel dispatch of the timed steps carries its own start/stop
+    # events (recorded by the library on the stream it launches on)
+    fcdp.fcdp_timing_enable(args.steps * L * 3 + 64)
+    sweeps = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        one_step(rec)
+        one_step(sweeps)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
 
-    k1_ms = sum(a.elapsed_time(b) for a, b in rec["k1"]) / (len(rec["k1"]) * L)
-    k3_ms = sum(a.elapsed_time(b) for a, b in rec["k3"]) / len(rec["k3"])
-    fwd_ms = sum(e0.elapsed_time(e1) for e0, e1, e2 in rec["sweeps"]) / args.steps
-    bwd_ms = sum(e1.elapsed_time(e2) for e0, e1, e2 in rec["sweeps"]) / args.steps
+    k1_kind = fcdp.KERNEL_UNFLATTEN
+    k1_launches, k1_total = fcdp.fcdp_timing_collect(k1_kind)
+    zc_launches, zc_total = fcdp.fcdp_timing_collect(fcdp.KERNEL_UNFLATTEN_ZEROCOPY)
+    k3_launches, k3_total = fcdp.fcdp_timing_collect(fcdp.KERNEL_REDUCE)
+    fcdp.fcdp_timing_enable(0)
+    k1_ms = k1_total / k1_launches
+    k3_ms = k3_total / k3_launches
+    fwd_ms = sum(e0.elapsed_time(e1) for e0, e1, e2 in sweeps) / args.steps
+    bwd_ms = sum(e1.elapsed_time(e2) for e0, e1, e2 in sweeps) / args.steps
     k1_bytes = 4 * N                        # read N*2 + write N*2
     k3_bytes = G * S * 4 + S * 4            # read G fp32 slices + write one
     k1_gbps = k1_bytes / (k1_ms * 1e-3) / 1e9
@@ -265,16 +262,18 @@ def main():
                                "unflatten + fp32 reduce of %d partials"
                                % (cfg.name, L, G, args.store, args.fetch, G),
                    "layer_bytes": layer_bytes, "fetch": args.fetch, "store": args.store},
-        "roofline": {"kernel": "copy_pieces (unflatten, device shards)", "bound": "hbm",
+        "roofline": {"kernel": "copy_pieces<1,3> (unflatten: forward from the gathered shards, "
+                               "backward from the DMA staging buffer)", "bound": "hbm",
                      "achieved": round(k1_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(k1_gbps / HBM_PEAK_GBPS, 4),
                      "traffic": MEASURED_TRAFFIC.get(cfg.name),
                      "bytes_per_launch": k1_bytes, "avg_launch_ms": round(k1_ms, 4),
-                     "launches_timed": len(rec["k1"]) * L},
+                     "launches_timed": k1_launches},
         "roofline_reduce": {"kernel": "reduce_ranks (fp32 in, fp32 out)", "bound": "hbm",
                             "achieved": round(k3_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                             "frac": round(k3_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
                             "bytes_per_launch": k3_bytes, "avg_launch_ms": round(k3_ms, 4),
+                            "launches_timed": k3_launches,
                             "bf16_out_gbps": round((G * S * 4 + S * 2) / (k3b_ms * 1e-3) / 1e9, 1)},
         "host_link": {"peak": LINK_PEAK_GBPS, "unit": "GB/s",
                       "forward_store_d2h": round(d2h_gbps, 2), "backward_fetch_h2d": round(h2d_gbps, 2),

@@ -267,6 +267,26 @@ const char *fcdp_last_error(void);
 fcdp_status fcdp_tuning_set(const char *name, int64_t value);
 int64_t fcdp_tuning_get(const char *name); /* -1 if unknown */
 
+/* Kernel timing for measurement.  While enabled, every kernel dispatch the
+ * library makes on the current device carries a start and a stop event that
+ * take the dispatch's own begin and end timestamps on its stream (at most
+ * `capacity` dispatches are kept; later ones are not timed).  fcdp_timing_collect waits for the recorded launches of
+ * one kind, returns how many there were and the sum of their durations in
+ * milliseconds, and forgets them.  fcdp_timing_enable(0) disables timing and
+ * frees the events.  Not thread-safe against concurrent data calls. */
+typedef enum {
+    FCDP_KERNEL_UNFLATTEN = 0,          /* shards or staging -> tensors */
+    FCDP_KERNEL_UNFLATTEN_ZEROCOPY = 1, /* mapped host cache -> tensors */
+    FCDP_KERNEL_FLATTEN = 2,
+    FCDP_KERNEL_REDUCE = 3,
+    FCDP_KERNEL_PACK = 4,
+    FCDP_KERNEL_UNPACK = 5,
+    FCDP_KERNEL_STORE_ZEROCOPY = 6,
+    FCDP_KERNEL_PROBE_COPY = 7
+} fcdp_kernel_kind;
+fcdp_status fcdp_timing_enable(int32_t capacity);
+fcdp_status fcdp_timing_collect(int32_t kind, int64_t *launches, double *total_ms);
+
 /* A plain contiguous device copy of `bytes` bytes with the same inner loop as
  * the scatter kernels; the known-size reference used to calibrate hardware
  * byte counters and to state the copy speed this GPU reaches. */

@@ -45,7 +45,8 @@ EXPORTS = [
     "fcdp_cache_state_forward_source", "fcdp_cache_state_backward_source",
     "fcdp_cache_state_optimizer_step", "fcdp_cache_state_is_dirty",
     "fcdp_status_string", "fcdp_last_error", "fcdp_tuning_set",
-    "fcdp_tuning_get", "fcdp_probe_copy",
+    "fcdp_tuning_get", "fcdp_probe_copy", "fcdp_timing_enable",
+    "fcdp_timing_collect",
 ]
 
 
@@ -114,6 +115,8 @@ def load_library() -> ctypes.CDLL:
     lib.fcdp_tuning_get.argtypes = [c.c_char_p]
     lib.fcdp_tuning_get.restype = i64
     lib.fcdp_probe_copy.argtypes = [vp, vp, c.c_size_t, vp]
+    lib.fcdp_timing_enable.argtypes = [i32]
+    lib.fcdp_timing_collect.argtypes = [i32, c.POINTER(i64), c.POINTER(c.c_double)]
     _lib = lib
     return lib
 
@@ -341,6 +344,28 @@ def fcdp_tuning_set(name: str, value: int) -> None:
 
 def fcdp_tuning_get(name: str) -> int:
     return load_library().fcdp_tuning_get(name.encode())
+
+
+KERNEL_UNFLATTEN = 0
+KERNEL_UNFLATTEN_ZEROCOPY = 1
+KERNEL_FLATTEN = 2
+KERNEL_REDUCE = 3
+KERNEL_PACK = 4
+KERNEL_UNPACK = 5
+KERNEL_STORE_ZEROCOPY = 6
+KERNEL_PROBE_COPY = 7
+
+
+def fcdp_timing_enable(capacity: int) -> None:
+    _check(load_library().fcdp_timing_enable(capacity))
+
+
+def fcdp_timing_collect(kind: int):
+    """(launches, total_ms) of the timed launches of one kernel kind."""
+    n = ctypes.c_int64()
+    ms = ctypes.c_double()
+    _check(load_library().fcdp_timing_collect(kind, ctypes.byref(n), ctypes.byref(ms)))
+    return n.value, ms.value
 
 
 def fcdp_probe_copy(dst, src, nbytes: int, stream=None) -> None:

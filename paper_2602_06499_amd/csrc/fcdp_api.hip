@@ -51,6 +51,40 @@ struct DeviceCtx {
 DeviceCtx g_ctx[fcdp::kMaxDevices];
 constexpr size_t kRing = 64;
 
+// ---------------------------------------------------------- kernel timing
+struct TimedLaunch {
+    int32_t kind;
+    hipEvent_t start, stop;
+};
+struct TimingCtx {
+    std::vector<hipEvent_t> pool;    // 2 * capacity timing events, created once
+    std::vector<TimedLaunch> taken;  // launches recorded so far
+    size_t next = 0;
+    bool on = false;
+};
+TimingCtx g_timing[fcdp::kMaxDevices];
+
+TimingCtx *timing_ctx()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= fcdp::kMaxDevices) return nullptr;
+    return &g_timing[dev];
+}
+
+// Hands out one start/stop pair for a launch of the given kind (nulls when
+// timing is off or the pool is used up).
+fcdp::LaunchEvents timing_events(int32_t kind)
+{
+    fcdp::LaunchEvents ev;
+    TimingCtx *c = timing_ctx();
+    if (!c || !c->on || c->next + 2 > c->pool.size()) return ev;
+    ev.start = c->pool[c->next];
+    ev.stop = c->pool[c->next + 1];
+    c->next += 2;
+    c->taken.push_back({kind, static_cast<hipEvent_t>(ev.start), static_cast<hipEvent_t>(ev.stop)});
+    return ev;
+}
+
 fcdp_status current_ctx(DeviceCtx **out)
 {
     int dev = 0;
@@ -156,7 +190,7 @@ fcdp_status run_windowed(const fcdp::PieceTable &tab, const fcdp::Piece *dev_pie
                          fcdp::TensorSide side, int32_t T,
                          const void *const *small, int32_t n_small,
                          const void *const *tensors, bool nt, int64_t wg_per_cu,
-                         hipStream_t st, const char *what, int64_t max_wgs = 0,
+                         hipStream_t st, const char *what, int32_t kind, int64_t max_wgs = 0,
                          int64_t block = 0)
 {
     const int64_t n_win = static_cast<int64_t>(tab.win_begin.size()) - 1;
@@ -176,6 +210,7 @@ fcdp_status run_windowed(const fcdp::PieceTable &tab, const fcdp::Piece *dev_pie
         c.wg_per_cu = wg_per_cu;
         c.max_wgs = max_wgs;
         c.block = block;
+        c.ev = timing_events(kind); // one pair per launch (per tensor window)
         hipError_t err = static_cast<hipError_t>(fcdp::launch_copy(c, st));
         if (err != hipSuccess) return hip_fail(err, what);
     }
@@ -320,6 +355,7 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
                 const int32_t n_copies = contiguous ? 1 : L->G;
                 const size_t each = contiguous ? flat_bytes : shard_bytes;
                 for (int32_t r = 0; r < n_copies; ++r) {
+                    shape.ev = timing_events(FCDP_KERNEL_STORE_ZEROCOPY);
                     hipError_t e = static_cast<hipError_t>(fcdp::launch_plain_copy(ha + r * each, shard_ptrs[r], each, copy, shape));
                     if (e != hipSuccess) return hip_fail(e, "launch zero-copy store");
                 }
@@ -333,7 +369,7 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
         for (int32_t r = 0; r < L->G; ++r) small[r] = shard_ptrs[r];
         return run_windowed(L->unflatten, tabs->unflatten, fcdp::TensorSide::Dst, L->T, small, L->G,
                             reinterpret_cast<const void *const *>(tensor_ptrs), tune.copy_nt != 0,
-                            tune.copy_wg_per_cu, compute, "launch unflatten");
+                            tune.copy_wg_per_cu, compute, "launch unflatten", FCDP_KERNEL_UNFLATTEN);
     }
     if (src == FCDP_SRC_HOST_DMA) {
         DeviceCtx::StagingUse *use = nullptr;
@@ -345,7 +381,7 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
         for (int32_t r = 0; r < L->G; ++r) small[r] = static_cast<const char *>(staging) + r * shard_bytes;
         st = run_windowed(L->unflatten, tabs->unflatten, fcdp::TensorSide::Dst, L->T, small, L->G,
                           reinterpret_cast<const void *const *>(tensor_ptrs), tune.copy_nt != 0,
-                          tune.copy_wg_per_cu, compute, "launch unflatten");
+                          tune.copy_wg_per_cu, compute, "launch unflatten", FCDP_KERNEL_UNFLATTEN);
         if (st != FCDP_OK) return st;
         FCDP_HIP(hipEventRecord(use->done, compute), "hipEventRecord(staging)");
         use->staging = staging;
@@ -356,7 +392,7 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
     for (int32_t r = 0; r < L->G; ++r) small[r] = static_cast<const char *>(zc_alias) + r * shard_bytes;
     return run_windowed(L->unflatten, tabs->unflatten, fcdp::TensorSide::Dst, L->T, small, L->G,
                         reinterpret_cast<const void *const *>(tensor_ptrs), false, 0, compute,
-                        "launch zero-copy unflatten", tune.link_max_wgs,
+                        "launch zero-copy unflatten", FCDP_KERNEL_UNFLATTEN_ZEROCOPY, tune.link_max_wgs,
                         tune.link_max_wgs > 0 ? tune.link_block : 0);
 }
 
@@ -375,7 +411,8 @@ fcdp_status fcdp_flatten_to_shards(const fcdp_layout *L, const void *const *tens
     for (int32_t r = 0; r < L->G; ++r) small[r] = shard_ptrs[r];
     const fcdp::Tuning &tune = fcdp::tuning();
     return run_windowed(L->flatten, tabs->flatten, fcdp::TensorSide::Src, L->T, small, L->G, tensor_ptrs,
-                        tune.copy_nt != 0, tune.copy_wg_per_cu, static_cast<hipStream_t>(stream), "launch flatten");
+                        tune.copy_nt != 0, tune.copy_wg_per_cu, static_cast<hipStream_t>(stream), "launch flatten",
+                        FCDP_KERNEL_FLATTEN);
 }
 
 fcdp_status fcdp_reduce_grad_shard(const void *const *partial_ptrs, int32_t G, int64_t elem_offset,
@@ -403,7 +440,8 @@ fcdp_status fcdp_reduce_grad_shard(const void *const *partial_ptrs, int32_t G, i
         if (overlap && !(pb == ob && ie == oe))
             return fail(FCDP_EINVAL, std::string(fn) + ": out_shard overlaps an input other than exactly in place");
     }
-    hipError_t e = static_cast<hipError_t>(fcdp::launch_reduce(partial_ptrs, G, elem_offset, count, in, out, out_shard, stream));
+    hipError_t e = static_cast<hipError_t>(fcdp::launch_reduce(partial_ptrs, G, elem_offset, count, in, out, out_shard, stream,
+                                                               count > 0 ? timing_events(FCDP_KERNEL_REDUCE) : fcdp::LaunchEvents()));
     if (e != hipSuccess) return hip_fail(e, "launch reduce");
     return FCDP_OK;
 }
@@ -433,6 +471,7 @@ static fcdp_status pack_or_unpack(const fcdp_layout *L, const void *src, void *d
     c.n_small = 2;
     c.nt = false;
     c.wg_per_cu = 0;
+    c.ev = timing_events(pack ? FCDP_KERNEL_PACK : FCDP_KERNEL_UNPACK);
     hipError_t e = static_cast<hipError_t>(fcdp::launch_copy(c, stream));
     if (e != hipSuccess) return hip_fail(e, fn);
     return FCDP_OK;
@@ -639,8 +678,56 @@ fcdp_status fcdp_probe_copy(void *dst, const void *src, size_t bytes, fcdp_strea
     if (!dst || !src) return fail(FCDP_EINVAL, "fcdp_probe_copy: NULL buffer");
     if (!aligned16(dst) || !aligned16(src)) return fail(FCDP_EALIGN, "fcdp_probe_copy: buffer not 16-byte aligned");
     if (bytes & 1) return fail(FCDP_EINVAL, "fcdp_probe_copy: bytes must be even");
-    hipError_t e = static_cast<hipError_t>(fcdp::launch_plain_copy(dst, src, bytes, stream));
+    fcdp::PlainCopy shape;
+    if (bytes) shape.ev = timing_events(FCDP_KERNEL_PROBE_COPY);
+    hipError_t e = static_cast<hipError_t>(fcdp::launch_plain_copy(dst, src, bytes, stream, shape));
     if (e != hipSuccess) return hip_fail(e, "launch plain copy");
+    return FCDP_OK;
+}
+
+fcdp_status fcdp_timing_enable(int32_t capacity)
+{
+    if (capacity < 0 || capacity > (1 << 20)) return fail(FCDP_EINVAL, "fcdp_timing_enable: capacity must be in 0..2^20");
+    TimingCtx *c = timing_ctx();
+    if (!c) return fail(FCDP_EHIP, "fcdp_timing_enable: no current device");
+    for (hipEvent_t e : c->pool) (void)hipEventDestroy(e);
+    c->pool.clear();
+    c->taken.clear();
+    c->next = 0;
+    c->on = false;
+    if (capacity == 0) return FCDP_OK;
+    c->pool.reserve(static_cast<size_t>(capacity) * 2);
+    for (int32_t i = 0; i < capacity * 2; ++i) {
+        hipEvent_t e;
+        hipError_t err = hipEventCreate(&e);
+        if (err != hipSuccess) return hip_fail(err, "hipEventCreate");
+        c->pool.push_back(e);
+    }
+    c->on = true;
+    return FCDP_OK;
+}
+
+fcdp_status fcdp_timing_collect(int32_t kind, int64_t *launches, double *total_ms)
+{
+    if (!launches || !total_ms) return fail(FCDP_EINVAL, "fcdp_timing_collect: NULL output");
+    *launches = 0;
+    *total_ms = 0.0;
+    TimingCtx *c = timing_ctx();
+    if (!c) return fail(FCDP_EHIP, "fcdp_timing_collect: no current device");
+    std::vector<TimedLaunch> keep;
+    for (const TimedLaunch &t : c->taken) {
+        if (t.kind != kind) {
+            keep.push_back(t);
+            continue;
+        }
+        FCDP_HIP(hipEventSynchronize(t.stop), "hipEventSynchronize");
+        float ms = 0.f;
+        FCDP_HIP(hipEventElapsedTime(&ms, t.start, t.stop), "hipEventElapsedTime");
+        *total_ms += ms;
+        *launches += 1;
+    }
+    c->taken.swap(keep);
+    if (c->taken.empty()) c->next = 0; // every event is free again
     return FCDP_OK;
 }
 

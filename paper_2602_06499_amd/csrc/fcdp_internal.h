@@ -95,6 +95,14 @@ Tuning &tuning();
 // host-side table construction (fcdp_layout.cpp)
 fcdp_status build_tables(fcdp_layout *L);
 
+// Timing events attached to one kernel dispatch (both null = untimed).  They
+// take the dispatch's own start and end timestamps, not those of barrier
+// packets around it.
+struct LaunchEvents {
+    void *start = nullptr; // hipEvent_t
+    void *stop = nullptr;
+};
+
 // kernel launchers (fcdp_kernels.hip).  All return a hipError_t as int.
 struct CopyLaunch {
     const Piece *pieces = nullptr;  // device
@@ -109,14 +117,16 @@ struct CopyLaunch {
     int64_t wg_per_cu = 0;
     int64_t max_wgs = 0;            // absolute cap on workgroups, 0 = none
     int64_t block = 0;              // threads per workgroup, 0 = copy_block
+    LaunchEvents ev;                // optional start/stop timing events
 };
 int launch_copy(const CopyLaunch &c, void *stream);
 int launch_reduce(const void *const *partials, int32_t G, int64_t elem_offset,
                   int64_t count, int in_dtype, int out_dtype, void *out,
-                  void *stream);
+                  void *stream, const LaunchEvents &ev = LaunchEvents());
 struct PlainCopy {
     int64_t chunk = 0, block = 0, unroll = 0, max_wgs = 0; // 0 = the copy_* knobs
     int nt = -1;                                           // -1 = copy_nt
+    LaunchEvents ev;
 };
 int launch_plain_copy(void *dst, const void *src, size_t bytes, void *stream,
                       const PlainCopy &shape = PlainCopy());

@@ -14,6 +14,7 @@
 // 16-byte coalesced access per lane, enough independent loads in flight per
 // wave to cover HBM latency, and equal bytes per workgroup.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cstdint>
 
@@ -198,15 +199,21 @@ __global__ void copy_pieces(const CopyArgs a)
     }
 }
 
+struct PlainArgs {
+    const char *src;
+    char *dst;
+    size_t bytes;
+    uint32_t chunk;
+};
+
 template <int UNROLL, int HINT>
-__global__ void plain_copy(const char *__restrict__ src, char *__restrict__ dst,
-                           size_t bytes, uint32_t chunk)
+__global__ void plain_copy(const PlainArgs a)
 {
-    const size_t n_chunks = (bytes + chunk - 1) / chunk;
+    const size_t n_chunks = (a.bytes + a.chunk - 1) / a.chunk;
     for (size_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
-        const size_t o = c * chunk;
-        const uint32_t n = static_cast<uint32_t>(bytes - o < chunk ? bytes - o : chunk);
-        copy_piece<UNROLL, HINT>(src + o, dst + o, n, false, threadIdx.x, blockDim.x);
+        const size_t o = c * a.chunk;
+        const uint32_t n = static_cast<uint32_t>(a.bytes - o < a.chunk ? a.bytes - o : a.chunk);
+        copy_piece<UNROLL, HINT>(a.src + o, a.dst + o, n, false, threadIdx.x, blockDim.x);
     }
 }
 
@@ -373,57 +380,63 @@ __global__ void __launch_bounds__(256) reduce_ranks(const ReduceArgs a)
 
 int g_cu_count[kMaxDevices] = {0};
 
-template <int UNROLL, int HINT>
-hipError_t launch_copy_t(const CopyArgs &args, dim3 grid, dim3 block, hipStream_t st)
+// Launches `kernel`; with timing events the dispatch itself carries them.
+template <typename K, typename A>
+hipError_t launch_one(K kernel, dim3 grid, dim3 block, hipStream_t st, const LaunchEvents &ev, const A &args)
 {
-    hipLaunchKernelGGL((copy_pieces<UNROLL, HINT>), grid, block, 0, st, args);
+    if (ev.start && ev.stop)
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, st, static_cast<hipEvent_t>(ev.start),
+                              static_cast<hipEvent_t>(ev.stop), 0, args);
+    else
+        hipLaunchKernelGGL(kernel, grid, block, 0, st, args);
     return hipGetLastError();
 }
 
 template <int UNROLL>
-hipError_t launch_copy_h(const CopyArgs &args, dim3 grid, dim3 block, int hint, hipStream_t st)
+hipError_t launch_copy_h(const CopyArgs &args, dim3 grid, dim3 block, int hint, hipStream_t st,
+                         const LaunchEvents &ev)
 {
     switch (hint & 3) {
-    case 0: return launch_copy_t<UNROLL, 0>(args, grid, block, st);
-    case 1: return launch_copy_t<UNROLL, 1>(args, grid, block, st);
-    case 2: return launch_copy_t<UNROLL, 2>(args, grid, block, st);
-    default: return launch_copy_t<UNROLL, 3>(args, grid, block, st);
+    case 0: return launch_one(copy_pieces<UNROLL, 0>, grid, block, st, ev, args);
+    case 1: return launch_one(copy_pieces<UNROLL, 1>, grid, block, st, ev, args);
+    case 2: return launch_one(copy_pieces<UNROLL, 2>, grid, block, st, ev, args);
+    default: return launch_one(copy_pieces<UNROLL, 3>, grid, block, st, ev, args);
     }
 }
 
 template <int UNROLL>
-hipError_t launch_plain_h(const char *s, char *d, size_t bytes, uint32_t chunk, dim3 grid,
-                          dim3 block, int hint, hipStream_t st)
+hipError_t launch_plain_h(const PlainArgs &args, dim3 grid, dim3 block, int hint, hipStream_t st,
+                          const LaunchEvents &ev)
 {
     switch (hint & 3) {
-    case 0: hipLaunchKernelGGL((plain_copy<UNROLL, 0>), grid, block, 0, st, s, d, bytes, chunk); break;
-    case 1: hipLaunchKernelGGL((plain_copy<UNROLL, 1>), grid, block, 0, st, s, d, bytes, chunk); break;
-    case 2: hipLaunchKernelGGL((plain_copy<UNROLL, 2>), grid, block, 0, st, s, d, bytes, chunk); break;
-    default: hipLaunchKernelGGL((plain_copy<UNROLL, 3>), grid, block, 0, st, s, d, bytes, chunk); break;
+    case 0: return launch_one(plain_copy<UNROLL, 0>, grid, block, st, ev, args);
+    case 1: return launch_one(plain_copy<UNROLL, 1>, grid, block, st, ev, args);
+    case 2: return launch_one(plain_copy<UNROLL, 2>, grid, block, st, ev, args);
+    default: return launch_one(plain_copy<UNROLL, 3>, grid, block, st, ev, args);
     }
-    return hipGetLastError();
 }
 
 template <int REM, bool IN_F32, bool OUT_F32, bool ALIGNED>
-hipError_t launch_reduce_r(const ReduceArgs &args, dim3 grid, dim3 block, hipStream_t st)
+hipError_t launch_reduce_r(const ReduceArgs &args, dim3 grid, dim3 block, hipStream_t st,
+                           const LaunchEvents &ev)
 {
-    hipLaunchKernelGGL((reduce_ranks<REM, IN_F32, OUT_F32, ALIGNED, kReduceUnroll, kReduceNT>),
-                       grid, block, 0, st, args);
-    return hipGetLastError();
+    return launch_one(reduce_ranks<REM, IN_F32, OUT_F32, ALIGNED, kReduceUnroll, kReduceNT>,
+                      grid, block, st, ev, args);
 }
 
 template <bool IN_F32, bool OUT_F32, bool ALIGNED>
-hipError_t launch_reduce_t(const ReduceArgs &args, dim3 grid, dim3 block, hipStream_t st)
+hipError_t launch_reduce_t(const ReduceArgs &args, dim3 grid, dim3 block, hipStream_t st,
+                           const LaunchEvents &ev)
 {
     switch (args.G % kGroup) {
-    case 0: return launch_reduce_r<0, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st);
-    case 1: return launch_reduce_r<1, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st);
-    case 2: return launch_reduce_r<2, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st);
-    case 3: return launch_reduce_r<3, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st);
-    case 4: return launch_reduce_r<4, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st);
-    case 5: return launch_reduce_r<5, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st);
-    case 6: return launch_reduce_r<6, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st);
-    default: return launch_reduce_r<7, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st);
+    case 0: return launch_reduce_r<0, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st, ev);
+    case 1: return launch_reduce_r<1, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st, ev);
+    case 2: return launch_reduce_r<2, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st, ev);
+    case 3: return launch_reduce_r<3, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st, ev);
+    case 4: return launch_reduce_r<4, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st, ev);
+    case 5: return launch_reduce_r<5, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st, ev);
+    case 6: return launch_reduce_r<6, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st, ev);
+    default: return launch_reduce_r<7, IN_F32, OUT_F32, ALIGNED>(args, grid, block, st, ev);
     }
 }
 
@@ -480,10 +493,10 @@ int launch_copy(const CopyLaunch &c, void *stream)
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int unroll = static_cast<int>(t.copy_unroll);
     const int hint = c.nt ? static_cast<int>(t.copy_nt) : 0;
-    if (unroll >= 8) return launch_copy_h<8>(args, g, b, hint, st);
-    if (unroll >= 4) return launch_copy_h<4>(args, g, b, hint, st);
-    if (unroll >= 2) return launch_copy_h<2>(args, g, b, hint, st);
-    return launch_copy_h<1>(args, g, b, hint, st);
+    if (unroll >= 8) return launch_copy_h<8>(args, g, b, hint, st, c.ev);
+    if (unroll >= 4) return launch_copy_h<4>(args, g, b, hint, st, c.ev);
+    if (unroll >= 2) return launch_copy_h<2>(args, g, b, hint, st, c.ev);
+    return launch_copy_h<1>(args, g, b, hint, st, c.ev);
 }
 
 int launch_plain_copy(void *dst, const void *src, size_t bytes, void *stream,
@@ -503,17 +516,20 @@ int launch_plain_copy(void *dst, const void *src, size_t bytes, void *stream,
         grid = std::min<int64_t>(grid, t.copy_wg_per_cu * device_cu_count());
     const dim3 g(static_cast<unsigned>(grid)), b(static_cast<unsigned>(block));
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const char *s = static_cast<const char *>(src);
-    char *d = static_cast<char *>(dst);
-    if (unroll >= 8) return launch_plain_h<8>(s, d, bytes, chunk, g, b, hint, st);
-    if (unroll >= 4) return launch_plain_h<4>(s, d, bytes, chunk, g, b, hint, st);
-    if (unroll >= 2) return launch_plain_h<2>(s, d, bytes, chunk, g, b, hint, st);
-    return launch_plain_h<1>(s, d, bytes, chunk, g, b, hint, st);
+    PlainArgs pa;
+    pa.src = static_cast<const char *>(src);
+    pa.dst = static_cast<char *>(dst);
+    pa.bytes = bytes;
+    pa.chunk = chunk;
+    if (unroll >= 8) return launch_plain_h<8>(pa, g, b, hint, st, shape.ev);
+    if (unroll >= 4) return launch_plain_h<4>(pa, g, b, hint, st, shape.ev);
+    if (unroll >= 2) return launch_plain_h<2>(pa, g, b, hint, st, shape.ev);
+    return launch_plain_h<1>(pa, g, b, hint, st, shape.ev);
 }
 
 int launch_reduce(const void *const *partials, int32_t G, int64_t elem_offset,
                   int64_t count, int in_dtype, int out_dtype, void *out,
-                  void *stream)
+                  void *stream, const LaunchEvents &ev)
 {
     if (count <= 0) return hipSuccess;
     const int64_t in_esz = in_dtype == FCDP_F32 ? 4 : 2;
@@ -539,16 +555,16 @@ int launch_reduce(const void *const *partials, int32_t G, int64_t elem_offset,
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool inf = in_dtype == FCDP_F32, outf = out_dtype == FCDP_F32;
     if (inf && outf)
-        return aligned ? launch_reduce_t<true, true, true>(args, g, b, st)
-                       : launch_reduce_t<true, true, false>(args, g, b, st);
+        return aligned ? launch_reduce_t<true, true, true>(args, g, b, st, ev)
+                       : launch_reduce_t<true, true, false>(args, g, b, st, ev);
     if (inf && !outf)
-        return aligned ? launch_reduce_t<true, false, true>(args, g, b, st)
-                       : launch_reduce_t<true, false, false>(args, g, b, st);
+        return aligned ? launch_reduce_t<true, false, true>(args, g, b, st, ev)
+                       : launch_reduce_t<true, false, false>(args, g, b, st, ev);
     if (!inf && outf)
-        return aligned ? launch_reduce_t<false, true, true>(args, g, b, st)
-                       : launch_reduce_t<false, true, false>(args, g, b, st);
-    return aligned ? launch_reduce_t<false, false, true>(args, g, b, st)
-                   : launch_reduce_t<false, false, false>(args, g, b, st);
+        return aligned ? launch_reduce_t<false, true, true>(args, g, b, st, ev)
+                       : launch_reduce_t<false, true, false>(args, g, b, st, ev);
+    return aligned ? launch_reduce_t<false, false, true>(args, g, b, st, ev)
+                   : launch_reduce_t<false, false, false>(args, g, b, st, ev);
 }
 
 } // namespace fcdp

@@ -407,3 +407,33 @@ def test_probe_copy():
     fcdp.fcdp_probe_copy(y, x, n, None)
     torch.cuda.synchronize()
     assert torch.equal(x, y)
+
+
+def test_kernel_timing_hooks():
+    """Timed dispatches are counted per kind and report plausible durations."""
+    n = 1 << 22
+    x = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")
+    y = torch.zeros_like(x)
+    parts = [torch.ones(n // 4, dtype=torch.float32, device="cuda") for _ in range(3)]
+    out = torch.zeros(n // 4, dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    fcdp.fcdp_timing_enable(8)
+    try:
+        for _ in range(3):
+            fcdp.fcdp_probe_copy(y, x, n, None)
+        fcdp.fcdp_reduce_grad_shard(parts, 3, 0, n // 4, fcdp.F32, fcdp.F32, out, None)
+        torch.cuda.synchronize()
+        cnt, ms = fcdp.fcdp_timing_collect(fcdp.KERNEL_PROBE_COPY)
+        assert cnt == 3 and 0.0 < ms < 50.0
+        cnt, ms = fcdp.fcdp_timing_collect(fcdp.KERNEL_REDUCE)
+        assert cnt == 1 and 0.0 < ms < 50.0
+        assert fcdp.fcdp_timing_collect(fcdp.KERNEL_PACK) == (0, 0.0)
+        # the pool is bounded: launches beyond the capacity are simply not timed
+        for _ in range(12):
+            fcdp.fcdp_probe_copy(y, x, n, None)
+        torch.cuda.synchronize()
+        cnt, ms = fcdp.fcdp_timing_collect(fcdp.KERNEL_PROBE_COPY)
+        assert cnt == 8
+    finally:
+        fcdp.fcdp_timing_enable(0)
+    assert torch.equal(x, y) and float(out[0]) == 3.0
