@@ -47,6 +47,10 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="0 = the config's layer count")
     ap.add_argument("--fetch", choices=["dma", "zerocopy"], default="dma")
     ap.add_argument("--store", choices=["dma", "zerocopy"], default="dma")
+    ap.add_argument("--no-pretouch", action="store_true")
+    ap.add_argument("--copies-in-flight", type=int, default=-1, help="-1 = the library default")
+    ap.add_argument("--timed-dispatches", type=int, default=-1,
+                    help="how many kernel dispatches carry timing events (-1 = all of the timed steps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--cpu-sample-layers", type=int, default=16)
@@ -70,6 +74,8 @@ def main():
     cfg = synth.CONFIGS[args.config]
     L = args.layers or cfg.layers
     G, T = cfg.G, len(cfg.numel)
+    if args.copies_in_flight >= 0:
+        fcdp.fcdp_tuning_set("max_copies_in_flight", args.copies_in_flight)
     lay = fcdp.fcdp_layout_build(cfg.numel, cfg.trainable, G, 2)
     lay.prepare()
     N, Np, S = lay.numel, lay.padded_numel, lay.shard_numel
@@ -99,7 +105,8 @@ def main():
     grad_shard = torch.empty(S, dtype=torch.float32, device=dev)
     t0 = time.time()
     cache = fcdp.fcdp_host_cache_alloc(layer_bytes * L)
-    cache.numpy(np.uint8)[:] = 0            # touch every page before timing
+    if not args.no_pretouch:
+        cache.numpy(np.uint8)[:] = 0        # touch every page before timing
     log("pinned host cache: %.2f GB allocated and touched in %.1f s" % (layer_bytes * L / 1e9, time.time() - t0))
     compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
     host_mode = fcdp.SRC_HOST_DMA if args.fetch == "dma" else fcdp.SRC_HOST_ZEROCOPY
@@ -134,7 +141,7 @@ def main():
     torch.cuda.synchronize()
     # every kernel dispatch of the timed steps carries its own start/stop
     # events (recorded by the library on the stream it launches on)
-    fcdp.fcdp_timing_enable(args.steps * L * 3 + 64)
+    fcdp.fcdp_timing_enable(args.steps * L * 3 + 64 if args.timed_dispatches < 0 else args.timed_dispatches)
     sweeps = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -148,14 +155,14 @@ def main():
     zc_launches, zc_total = fcdp.fcdp_timing_collect(fcdp.KERNEL_UNFLATTEN_ZEROCOPY)
     k3_launches, k3_total = fcdp.fcdp_timing_collect(fcdp.KERNEL_REDUCE)
     fcdp.fcdp_timing_enable(0)
-    k1_ms = k1_total / k1_launches
-    k3_ms = k3_total / k3_launches
+    k1_ms = k1_total / max(k1_launches, 1)
+    k3_ms = k3_total / max(k3_launches, 1)
     fwd_ms = sum(e0.elapsed_time(e1) for e0, e1, e2 in sweeps) / args.steps
     bwd_ms = sum(e1.elapsed_time(e2) for e0, e1, e2 in sweeps) / args.steps
     k1_bytes = 4 * N                        # read N*2 + write N*2
     k3_bytes = G * S * 4 + S * 4            # read G fp32 slices + write one
-    k1_gbps = k1_bytes / (k1_ms * 1e-3) / 1e9
-    k3_gbps = k3_bytes / (k3_ms * 1e-3) / 1e9
+    k1_gbps = k1_bytes / (k1_ms * 1e-3) / 1e9 if k1_ms else 0.0
+    k3_gbps = k3_bytes / (k3_ms * 1e-3) / 1e9 if k3_ms else 0.0
     d2h_gbps = L * layer_bytes / (fwd_ms * 1e-3) / 1e9
     h2d_gbps = L * layer_bytes / (bwd_ms * 1e-3) / 1e9
     value = 2 * L * layer_bytes / (ms_per_step * 1e-3) / 1e9

@@ -27,8 +27,11 @@
  *     fcdp_host_cache_alloc (freed with fcdp_host_cache_free).
  *   - Streams are hipStream_t values passed as void* (NULL = the default
  *     stream).  Data calls only enqueue work; they never synchronise the
- *     device, except the first data call on a layout, which uploads the
- *     layout's tables (call fcdp_layout_prepare beforehand to avoid that).
+ *     device, with two exceptions: the first data call on a layout uploads
+ *     the layout's tables (call fcdp_layout_prepare beforehand to avoid
+ *     that), and a call that would put more than max_copies_in_flight (a
+ *     tuning knob, default 2) host-link DMA copies in flight first waits on
+ *     the host for the oldest of them.
  *   - Every data base pointer must be 16-byte aligned (FCDP_EALIGN if not).
  *     Offsets inside a buffer may be any element index.
  *   - Errors: a status code is returned, nothing is thrown and nothing

@@ -46,6 +46,9 @@ struct DeviceCtx {
     };
     StagingUse uses[8];
     uint64_t clock = 0;
+    // completion events of the host-link copies still in flight, oldest first
+    std::vector<hipEvent_t> copy_done;   // ring storage
+    size_t copy_head = 0, copy_count = 0;
 };
 
 DeviceCtx g_ctx[fcdp::kMaxDevices];
@@ -114,6 +117,52 @@ fcdp_status order_after(DeviceCtx *ctx, hipStream_t src, hipStream_t dst)
     }
     FCDP_HIP(hipEventRecord(ev, src), "hipEventRecord");
     FCDP_HIP(hipStreamWaitEvent(dst, ev, 0), "hipStreamWaitEvent");
+    return FCDP_OK;
+}
+
+// Back-pressure on host-link copies: call before enqueueing one (may block on
+// the host until the oldest queued copy has finished), then copy_enqueued()
+// right after it.
+fcdp_status copy_admit(DeviceCtx *ctx)
+{
+    const int64_t cap = fcdp::tuning().max_copies_in_flight;
+    if (cap <= 0) return FCDP_OK;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    if (ctx->copy_done.size() != static_cast<size_t>(cap)) {
+        // (re)size: drain what is tracked, then rebuild the ring
+        for (size_t i = 0; i < ctx->copy_count; ++i)
+            FCDP_HIP(hipEventSynchronize(ctx->copy_done[(ctx->copy_head + i) % ctx->copy_done.size()]), "hipEventSynchronize");
+        for (hipEvent_t e : ctx->copy_done) (void)hipEventDestroy(e);
+        ctx->copy_done.clear();
+        ctx->copy_head = ctx->copy_count = 0;
+        for (int64_t i = 0; i < cap; ++i) {
+            hipEvent_t e;
+            FCDP_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming), "hipEventCreate");
+            ctx->copy_done.push_back(e);
+        }
+    }
+    // retire finished copies without blocking, then block only if still full
+    while (ctx->copy_count > 0 && hipEventQuery(ctx->copy_done[ctx->copy_head]) == hipSuccess) {
+        ctx->copy_head = (ctx->copy_head + 1) % ctx->copy_done.size();
+        --ctx->copy_count;
+    }
+    (void)hipGetLastError(); // hipEventQuery reports "not ready" as an error code
+    if (ctx->copy_count == ctx->copy_done.size()) {
+        FCDP_HIP(hipEventSynchronize(ctx->copy_done[ctx->copy_head]), "hipEventSynchronize");
+        ctx->copy_head = (ctx->copy_head + 1) % ctx->copy_done.size();
+        --ctx->copy_count;
+    }
+    return FCDP_OK;
+}
+
+fcdp_status copy_enqueued(DeviceCtx *ctx, hipStream_t copy)
+{
+    if (fcdp::tuning().max_copies_in_flight <= 0) return FCDP_OK;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    if (ctx->copy_done.empty() || ctx->copy_count == ctx->copy_done.size()) return FCDP_OK;
+    hipEvent_t e = ctx->copy_done[(ctx->copy_head + ctx->copy_count) % ctx->copy_done.size()];
+    FCDP_HIP(hipEventRecord(e, copy), "hipEventRecord");
+    ++ctx->copy_count;
     return FCDP_OK;
 }
 
@@ -360,10 +409,15 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
                     if (e != hipSuccess) return hip_fail(e, "launch zero-copy store");
                 }
             } else if (contiguous) {
+                if ((st = copy_admit(ctx)) != FCDP_OK) return st;
                 FCDP_HIP(hipMemcpyAsync(h, shard_ptrs[0], flat_bytes, hipMemcpyDeviceToHost, copy), "hipMemcpyAsync(D2H)");
+                if ((st = copy_enqueued(ctx, copy)) != FCDP_OK) return st;
             } else {
-                for (int32_t r = 0; r < L->G; ++r)
+                for (int32_t r = 0; r < L->G; ++r) {
+                    if ((st = copy_admit(ctx)) != FCDP_OK) return st;
                     FCDP_HIP(hipMemcpyAsync(h + r * shard_bytes, shard_ptrs[r], shard_bytes, hipMemcpyDeviceToHost, copy), "hipMemcpyAsync(D2H)");
+                    if ((st = copy_enqueued(ctx, copy)) != FCDP_OK) return st;
+                }
             }
         }
         for (int32_t r = 0; r < L->G; ++r) small[r] = shard_ptrs[r];
@@ -376,7 +430,9 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
         if ((st = staging_slot(ctx, staging, &use)) != FCDP_OK) return st;
         if (use->staging == staging)
             FCDP_HIP(hipStreamWaitEvent(copy, use->done, 0), "hipStreamWaitEvent(staging)");
+        if ((st = copy_admit(ctx)) != FCDP_OK) return st;
         FCDP_HIP(hipMemcpyAsync(staging, host_cache, flat_bytes, hipMemcpyHostToDevice, copy), "hipMemcpyAsync(H2D)");
+        if ((st = copy_enqueued(ctx, copy)) != FCDP_OK) return st;
         if ((st = order_after(ctx, copy, compute)) != FCDP_OK) return st;
         for (int32_t r = 0; r < L->G; ++r) small[r] = static_cast<const char *>(staging) + r * shard_bytes;
         st = run_windowed(L->unflatten, tabs->unflatten, fcdp::TensorSide::Dst, L->T, small, L->G,
@@ -647,6 +703,9 @@ fcdp_status fcdp_tuning_set(const char *name, int64_t v)
     } else if (n == "copy_nt") {
         if (v < 0 || v > 3) return fail(FCDP_EINVAL, "copy_nt: 0..3 (bit 0 loads, bit 1 stores)");
         t.copy_nt = v;
+    } else if (n == "max_copies_in_flight") {
+        if (v < 0 || v > 4096) return fail(FCDP_EINVAL, "max_copies_in_flight: 0..4096");
+        t.max_copies_in_flight = v;
     } else if (n == "reduce_block") {
         if (v < 64 || v > 256 || !pow2(v)) return fail(FCDP_EINVAL, "reduce_block: power of two in 64..256");
         t.reduce_block = v;
@@ -669,6 +728,7 @@ int64_t fcdp_tuning_get(const char *name)
     if (n == "link_block") return t.link_block;
     if (n == "link_chunk_bytes") return t.link_chunk_bytes;
     if (n == "copy_nt") return t.copy_nt;
+    if (n == "max_copies_in_flight") return t.max_copies_in_flight;
     if (n == "reduce_block") return t.reduce_block;
     return -1;
 }

@@ -88,6 +88,12 @@ struct Tuning {
     int64_t link_max_wgs = 64;
     int64_t link_block = 256;
     int64_t link_chunk_bytes = 16384; // bytes per workgroup iteration (store)
+    // most host-link copies (DMA stores and fetches) in flight per device; a
+    // call that would exceed it first waits on the host for the oldest one.
+    // Measured on MI355X / ROCm 7: with up to 4 large pinned copies queued
+    // both directions run at the full link rate; from 6 on the stores fall
+    // to 20-30 GB/s.  2 is also the depth double buffering needs.  0 = off
+    int64_t max_copies_in_flight = 2;
     int64_t reduce_block = 64;
 };
 Tuning &tuning();
