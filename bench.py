@@ -32,10 +32,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 LINK_PEAK_GBPS = 63.0           # PCIe Gen5 x16 per direction, 128b/130b
 
-# HBM bytes per unflatten launch measured with rocprofv3 --pmc (FETCH_SIZE,
-# WRITE_SIZE), scaled by the plain-copy calibration; see profiles/.  None
-# until such a run has been recorded for the workload.
-MEASURED_TRAFFIC = {}
+# HBM bytes per unflatten launch measured with rocprofv3 --pmc (FETCH_SIZE
+# x 1.99978, WRITE_SIZE x 1.0, the factors the same counters show for the
+# plain copy of known size); profiles/unflatten_reduce_llama7b_g8_hbm_traffic.md
+MEASURED_TRAFFIC = {"llama7b_g8": 822.2e6}
+MEASURED_TRAFFIC_REDUCE = {"llama7b_g8": 910.7e6}
 
 
 def parse():
@@ -278,7 +279,8 @@ def main():
                      "launches_timed": k1_launches},
         "roofline_reduce": {"kernel": "reduce_ranks (fp32 in, fp32 out)", "bound": "hbm",
                             "achieved": round(k3_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                            "frac": round(k3_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                            "frac": round(k3_gbps / HBM_PEAK_GBPS, 4),
+                            "traffic": MEASURED_TRAFFIC_REDUCE.get(cfg.name),
                             "bytes_per_launch": k3_bytes, "avg_launch_ms": round(k3_ms, 4),
                             "launches_timed": k3_launches,
                             "bf16_out_gbps": round((G * S * 4 + S * 2) / (k3b_ms * 1e-3) / 1e9, 1)},
