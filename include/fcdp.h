@@ -70,7 +70,8 @@ typedef enum { FCDP_BF16 = 0, FCDP_F32 = 1 } fcdp_dtype;
 typedef enum {
     FCDP_SRC_DEVICE_SHARDS = 0, /* cache miss: scatter the G gathered shards */
     FCDP_SRC_HOST_DMA = 1,      /* cache hit: DMA host cache -> staging, scatter */
-    FCDP_SRC_HOST_ZEROCOPY = 2  /* cache hit: kernel reads the mapped host cache */
+    FCDP_SRC_HOST_ZEROCOPY = 2, /* cache hit: kernel reads the mapped host cache */
+    FCDP_SRC_DEVICE_RESIDENT = 3 /* kept on the device since the forward pass: nothing to do */
 } fcdp_source;
 
 /* store_cache argument of fcdp_materialize_layer */
@@ -170,6 +171,16 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *layout, fcdp_source src,
                                    void *const *tensor_ptrs, int store_cache,
                                    fcdp_stream compute, fcdp_stream copy);
 
+/* The cache store alone (Alg. 1 "H[p] <- p"), for callers that decide after
+ * the layer's forward computation whether to offload it (Sec. 4.4): copies
+ * concat(shard_0..shard_{G-1}) to host_cache on `copy`, ordered after what is
+ * enqueued on `compute` at the time of the call.  store_mode is FCDP_STORE_DMA
+ * or FCDP_STORE_ZEROCOPY; arguments as for fcdp_materialize_layer. */
+fcdp_status fcdp_cache_store(const fcdp_layout *layout,
+                             const void *const *shard_ptrs, void *host_cache,
+                             int store_mode, fcdp_stream compute,
+                             fcdp_stream copy);
+
 /* Inverse of the scatter, for initialisation and tests: writes the G shards
  * from the T tensors and zero-fills the tail padding. */
 fcdp_status fcdp_flatten_to_shards(const fcdp_layout *layout,
@@ -257,6 +268,30 @@ fcdp_status fcdp_cache_state_optimizer_step(fcdp_cache_state *state);
 /* 1 dirty, 0 clean, -1 bad argument */
 int32_t fcdp_cache_state_is_dirty(const fcdp_cache_state *state, int32_t layer,
                                   int32_t klass);
+
+/* Adaptive placement (Sec. 4.4 "Adaptive GPU Caching").  tau in [0, 1]; the
+ * default 0 offloads every layer (the plain schedule of Sec. 4.3).
+ * fcdp_cache_state_place is the decision at the "cache on CPU" point of a
+ * layer, after its forward computation: utilisation = used_bytes /
+ * total_bytes of device memory as the caller measures it at that moment.
+ *   *keep = 1  utilisation < tau: the layer's parameters stay on the device
+ *              until its backward pass; the caller issues neither store nor
+ *              fetch, backward_source answers FCDP_SRC_DEVICE_RESIDENT, and
+ *              every class that forward_source had just handed out for
+ *              storing is dirty again (the host copy was not refreshed);
+ *   *keep = 0  offload as usual (the caller issues the store now).
+ * fcdp_cache_state_release ends a layer's residency (after its backward
+ * pass); fcdp_cache_state_optimizer_step ends all of them. */
+fcdp_status fcdp_cache_state_set_tau(fcdp_cache_state *state, double tau);
+fcdp_status fcdp_cache_state_place(fcdp_cache_state *state, int32_t layer,
+                                   int64_t used_bytes, int64_t total_bytes,
+                                   int32_t *keep);
+fcdp_status fcdp_cache_state_release(fcdp_cache_state *state, int32_t layer);
+
+/* Bytes this process has sent over the host link through the library on the
+ * current device since the last reset: cache stores (device to host) and
+ * cache fetches (host to device), DMA and zero-copy alike. */
+fcdp_status fcdp_link_bytes(int32_t reset, int64_t *stored, int64_t *fetched);
 
 /* ------------------------------------------------------------------- misc */
 const char *fcdp_status_string(fcdp_status status);

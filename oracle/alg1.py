@@ -72,3 +72,30 @@ def replay(layers: Sequence[Sequence[Tuple[str, int, bool]]],
         vol.append(v)
     return {"events": events, "inter_elems": vol, "stale_reads": stale_reads,
             "dirty": dict(dirty)}
+
+
+def replay_adaptive(layer_bytes: Sequence[int], utilisation, tau: float,
+                    iterations: int) -> Dict[str, object]:
+    """Adaptive GPU caching on top of the full fine-tuning schedule (Sec. 4.4).
+
+    layer_bytes[l]: bytes of layer l's parameters; utilisation(it, l): device
+    memory utilisation in [0, 1] seen at the "cache on CPU" point of layer l,
+    after its forward computation.  Below tau the layer stays on the device
+    (no store, no load in the backward pass); otherwise it is stored to the
+    host cache and loaded back for the backward pass.  Every parameter is
+    trainable, so every forward pass starts from the gathered shards.
+    Returns per-iteration kept layers and bytes over the host link.
+    """
+    out = []
+    for it in range(iterations):
+        kept, stored, fetched = [], 0, 0
+        for l, nbytes in enumerate(layer_bytes):        # forward
+            if utilisation(it, l) < tau:
+                kept.append(l)
+            else:
+                stored += nbytes
+        for l in range(len(layer_bytes) - 1, -1, -1):   # backward
+            if l not in kept:
+                fetched += layer_bytes[l]
+        out.append({"kept": kept, "stored": stored, "fetched": fetched})
+    return {"iterations": out}

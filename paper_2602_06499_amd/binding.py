@@ -17,6 +17,7 @@ F32 = 1
 SRC_DEVICE_SHARDS = 0
 SRC_HOST_DMA = 1
 SRC_HOST_ZEROCOPY = 2
+SRC_DEVICE_RESIDENT = 3
 STORE_NONE = 0
 STORE_DMA = 1
 STORE_ZEROCOPY = 2
@@ -38,12 +39,14 @@ EXPORTS = [
     "fcdp_layout_trainable_numel", "fcdp_layout_packed_numel",
     "fcdp_layout_offsets", "fcdp_layout_segments", "fcdp_layout_copy_plan",
     "fcdp_layout_prepare",
-    "fcdp_materialize_layer", "fcdp_flatten_to_shards",
+    "fcdp_materialize_layer", "fcdp_cache_store", "fcdp_flatten_to_shards",
     "fcdp_reduce_grad_shard", "fcdp_pack_trainable", "fcdp_unpack_trainable",
     "fcdp_host_cache_alloc", "fcdp_host_cache_free",
     "fcdp_cache_state_create", "fcdp_cache_state_destroy",
     "fcdp_cache_state_forward_source", "fcdp_cache_state_backward_source",
     "fcdp_cache_state_optimizer_step", "fcdp_cache_state_is_dirty",
+    "fcdp_cache_state_set_tau", "fcdp_cache_state_place",
+    "fcdp_cache_state_release", "fcdp_link_bytes",
     "fcdp_status_string", "fcdp_last_error", "fcdp_tuning_set",
     "fcdp_tuning_get", "fcdp_probe_copy", "fcdp_timing_enable",
     "fcdp_timing_collect",
@@ -94,6 +97,11 @@ def load_library() -> ctypes.CDLL:
     lib.fcdp_layout_prepare.argtypes = [vp]
     lib.fcdp_materialize_layer.argtypes = [vp, c.c_int, vp, vp, vp, vp, c.c_int, vp, vp]
     lib.fcdp_flatten_to_shards.argtypes = [vp, vp, vp, vp]
+    lib.fcdp_cache_store.argtypes = [vp, vp, vp, c.c_int, vp, vp]
+    lib.fcdp_cache_state_set_tau.argtypes = [vp, c.c_double]
+    lib.fcdp_cache_state_place.argtypes = [vp, i32, i64, i64, c.POINTER(i32)]
+    lib.fcdp_cache_state_release.argtypes = [vp, i32]
+    lib.fcdp_link_bytes.argtypes = [i32, c.POINTER(i64), c.POINTER(i64)]
     lib.fcdp_reduce_grad_shard.argtypes = [vp, i32, i64, i64, c.c_int, c.c_int, vp, vp]
     lib.fcdp_pack_trainable.argtypes = [vp, vp, vp, vp]
     lib.fcdp_unpack_trainable.argtypes = [vp, vp, vp, vp]
@@ -236,6 +244,20 @@ def fcdp_materialize_layer(layout: Layout, src: int, shard_ptrs, host_cache,
         _stream(compute), _stream(copy)))
 
 
+def fcdp_cache_store(layout: Layout, shard_ptrs, host_cache, store_mode=STORE_DMA,
+                     compute=None, copy=None) -> None:
+    _check(load_library().fcdp_cache_store(
+        layout.handle, _ptr_array(shard_ptrs), _ptr(host_cache), int(store_mode),
+        _stream(compute), _stream(copy)))
+
+
+def fcdp_link_bytes(reset: bool = False):
+    """(stored, fetched) bytes sent over the host link through the library."""
+    a, b = ctypes.c_int64(), ctypes.c_int64()
+    _check(load_library().fcdp_link_bytes(int(reset), ctypes.byref(a), ctypes.byref(b)))
+    return a.value, b.value
+
+
 def fcdp_flatten_to_shards(layout: Layout, tensor_ptrs, shard_ptrs,
                            stream=None) -> None:
     _check(load_library().fcdp_flatten_to_shards(
@@ -325,6 +347,18 @@ class CacheState:
 
     def optimizer_step(self) -> None:
         _check(load_library().fcdp_cache_state_optimizer_step(self.handle))
+
+    def set_tau(self, tau: float) -> None:
+        _check(load_library().fcdp_cache_state_set_tau(self.handle, tau))
+
+    def place(self, layer: int, used_bytes: int, total_bytes: int) -> bool:
+        keep = ctypes.c_int32()
+        _check(load_library().fcdp_cache_state_place(
+            self.handle, layer, used_bytes, total_bytes, ctypes.byref(keep)))
+        return bool(keep.value)
+
+    def release(self, layer: int) -> None:
+        _check(load_library().fcdp_cache_state_release(self.handle, layer))
 
     def is_dirty(self, layer: int, klass: int) -> int:
         return load_library().fcdp_cache_state_is_dirty(self.handle, layer, klass)

@@ -47,6 +47,7 @@ struct DeviceCtx {
     StagingUse uses[8];
     uint64_t clock = 0;
     // completion events of the host-link copies still in flight, oldest first
+    int64_t stored_bytes = 0, fetched_bytes = 0;
     std::vector<hipEvent_t> copy_done;   // ring storage
     size_t copy_head = 0, copy_count = 0;
 };
@@ -287,6 +288,71 @@ fcdp_status check_shard_ptrs(const fcdp_layout *L, const void *const *shard_ptrs
     return FCDP_OK;
 }
 
+// Device address of a mapped pinned host buffer, or FCDP_ENOTPINNED.
+fcdp_status mapped_alias(void *host, const char *fn, void **alias)
+{
+    hipPointerAttribute_t attr;
+    std::memset(&attr, 0, sizeof attr);
+    hipError_t e = hipPointerGetAttributes(&attr, host);
+    if (e != hipSuccess) {
+        (void)hipGetLastError(); // clear the sticky error of an unknown pointer
+        return fail(FCDP_ENOTPINNED, std::string(fn) + ": host_cache is not known to HIP as pinned host memory");
+    }
+    if (attr.type != hipMemoryTypeHost || !attr.devicePointer)
+        return fail(FCDP_ENOTPINNED, std::string(fn) + ": host_cache is not mapped pinned host memory");
+    *alias = attr.devicePointer;
+    return FCDP_OK;
+}
+
+// H <- concat(shards): after the producers of the shards (everything on
+// `compute` so far), on the `copy` stream.
+fcdp_status enqueue_store(const fcdp_layout *L, DeviceCtx *ctx, const void *const *shard_ptrs,
+                          void *host_cache, void *store_alias, int store_cache,
+                          hipStream_t compute, hipStream_t copy)
+{
+    const fcdp::Tuning &tune = fcdp::tuning();
+    const size_t flat_bytes = static_cast<size_t>(L->N_pad) * L->esz;
+    const size_t shard_bytes = static_cast<size_t>(L->S) * L->esz;
+    fcdp_status st;
+    // H <- concat(shards): after the producers of the shards, beside the scatter
+    if ((st = order_after(ctx, compute, copy)) != FCDP_OK) return st;
+    char *h = static_cast<char *>(host_cache);
+    // contiguous shards (one gather buffer) go out as a single copy
+    bool contiguous = true;
+    for (int32_t r = 1; r < L->G; ++r)
+        if (static_cast<const char *>(shard_ptrs[r]) != static_cast<const char *>(shard_ptrs[0]) + r * shard_bytes)
+            contiguous = false;
+    if (store_cache == FCDP_STORE_ZEROCOPY) {
+        // a few workgroups write the image through the host mapping
+        fcdp::PlainCopy shape;
+        shape.chunk = tune.link_chunk_bytes;
+        shape.block = tune.link_block;
+        shape.unroll = 4;
+        shape.max_wgs = tune.link_max_wgs;
+        shape.nt = 0;
+        char *ha = static_cast<char *>(store_alias);
+        const int32_t n_copies = contiguous ? 1 : L->G;
+        const size_t each = contiguous ? flat_bytes : shard_bytes;
+        for (int32_t r = 0; r < n_copies; ++r) {
+            shape.ev = timing_events(FCDP_KERNEL_STORE_ZEROCOPY);
+            hipError_t e = static_cast<hipError_t>(fcdp::launch_plain_copy(ha + r * each, shard_ptrs[r], each, copy, shape));
+            if (e != hipSuccess) return hip_fail(e, "launch zero-copy store");
+        }
+    } else if (contiguous) {
+        if ((st = copy_admit(ctx)) != FCDP_OK) return st;
+        FCDP_HIP(hipMemcpyAsync(h, shard_ptrs[0], flat_bytes, hipMemcpyDeviceToHost, copy), "hipMemcpyAsync(D2H)");
+        if ((st = copy_enqueued(ctx, copy)) != FCDP_OK) return st;
+    } else {
+        for (int32_t r = 0; r < L->G; ++r) {
+            if ((st = copy_admit(ctx)) != FCDP_OK) return st;
+            FCDP_HIP(hipMemcpyAsync(h + r * shard_bytes, shard_ptrs[r], shard_bytes, hipMemcpyDeviceToHost, copy), "hipMemcpyAsync(D2H)");
+            if ((st = copy_enqueued(ctx, copy)) != FCDP_OK) return st;
+        }
+    }
+    ctx->stored_bytes += static_cast<int64_t>(flat_bytes);
+    return FCDP_OK;
+}
+
 } // namespace
 
 extern "C" {
@@ -322,12 +388,18 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
 {
     const char *fn = "fcdp_materialize_layer";
     if (!L) return fail(FCDP_EINVAL, std::string(fn) + ": layout is NULL");
-    if (src != FCDP_SRC_DEVICE_SHARDS && src != FCDP_SRC_HOST_DMA && src != FCDP_SRC_HOST_ZEROCOPY)
+    if (src != FCDP_SRC_DEVICE_SHARDS && src != FCDP_SRC_HOST_DMA && src != FCDP_SRC_HOST_ZEROCOPY &&
+        src != FCDP_SRC_DEVICE_RESIDENT)
         return fail(FCDP_EINVAL, std::string(fn) + ": unknown source");
     if (store_cache != FCDP_STORE_NONE && store_cache != FCDP_STORE_DMA && store_cache != FCDP_STORE_ZEROCOPY)
         return fail(FCDP_EINVAL, std::string(fn) + ": unknown store_cache mode");
     fcdp_status st = check_tensor_ptrs(L, reinterpret_cast<const void *const *>(tensor_ptrs), fn);
     if (st != FCDP_OK) return st;
+    if (src == FCDP_SRC_DEVICE_RESIDENT) {
+        // the tensors still hold the layer since its forward pass
+        if (store_cache) return fail(FCDP_EINVAL, std::string(fn) + ": store_cache is only valid with FCDP_SRC_DEVICE_SHARDS");
+        return FCDP_OK;
+    }
     hipStream_t compute = static_cast<hipStream_t>(compute_);
     hipStream_t copy = static_cast<hipStream_t>(copy_);
     const size_t flat_bytes = static_cast<size_t>(L->N_pad) * L->esz;
@@ -346,32 +418,14 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
             if (!staging) return fail(FCDP_EINVAL, std::string(fn) + ": FCDP_SRC_HOST_DMA needs a staging buffer");
             if (!aligned16(staging)) return fail(FCDP_EALIGN, std::string(fn) + ": staging is not 16-byte aligned");
         } else if (flat_bytes) {
-            hipPointerAttribute_t attr;
-            std::memset(&attr, 0, sizeof attr);
-            hipError_t e = hipPointerGetAttributes(&attr, host_cache);
-            if (e != hipSuccess) {
-                (void)hipGetLastError(); // clear the sticky error of an unknown pointer
-                return fail(FCDP_ENOTPINNED, std::string(fn) + ": host_cache is not known to HIP as pinned host memory");
-            }
-            if (attr.type != hipMemoryTypeHost || !attr.devicePointer)
-                return fail(FCDP_ENOTPINNED, std::string(fn) + ": host_cache is not mapped pinned host memory");
-            zc_alias = attr.devicePointer;
+            if ((st = mapped_alias(host_cache, fn, &zc_alias)) != FCDP_OK) return st;
         }
     }
     if (store_cache && !aligned16(host_cache))
         return fail(FCDP_EALIGN, std::string(fn) + ": host_cache is not 16-byte aligned");
     void *store_alias = nullptr;
     if (store_cache == FCDP_STORE_ZEROCOPY && flat_bytes) {
-        hipPointerAttribute_t attr;
-        std::memset(&attr, 0, sizeof attr);
-        hipError_t e = hipPointerGetAttributes(&attr, host_cache);
-        if (e != hipSuccess) {
-            (void)hipGetLastError();
-            return fail(FCDP_ENOTPINNED, std::string(fn) + ": host_cache is not known to HIP as pinned host memory");
-        }
-        if (attr.type != hipMemoryTypeHost || !attr.devicePointer)
-            return fail(FCDP_ENOTPINNED, std::string(fn) + ": host_cache is not mapped pinned host memory");
-        store_alias = attr.devicePointer;
+        if ((st = mapped_alias(host_cache, fn, &store_alias)) != FCDP_OK) return st;
     }
     if (L->N == 0 && !(store_cache && flat_bytes)) return FCDP_OK;
 
@@ -384,41 +438,8 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
     const void *small[FCDP_MAX_G];
     if (src == FCDP_SRC_DEVICE_SHARDS) {
         if (store_cache && flat_bytes) {
-            // H <- concat(shards): after the producers of the shards, beside the scatter
-            if ((st = order_after(ctx, compute, copy)) != FCDP_OK) return st;
-            char *h = static_cast<char *>(host_cache);
-            // contiguous shards (one gather buffer) go out as a single copy
-            bool contiguous = true;
-            for (int32_t r = 1; r < L->G; ++r)
-                if (static_cast<const char *>(shard_ptrs[r]) != static_cast<const char *>(shard_ptrs[0]) + r * shard_bytes)
-                    contiguous = false;
-            if (store_cache == FCDP_STORE_ZEROCOPY) {
-                // a few workgroups write the image through the host mapping
-                fcdp::PlainCopy shape;
-                shape.chunk = tune.link_chunk_bytes;
-                shape.block = tune.link_block;
-                shape.unroll = 4;
-                shape.max_wgs = tune.link_max_wgs;
-                shape.nt = 0;
-                char *ha = static_cast<char *>(store_alias);
-                const int32_t n_copies = contiguous ? 1 : L->G;
-                const size_t each = contiguous ? flat_bytes : shard_bytes;
-                for (int32_t r = 0; r < n_copies; ++r) {
-                    shape.ev = timing_events(FCDP_KERNEL_STORE_ZEROCOPY);
-                    hipError_t e = static_cast<hipError_t>(fcdp::launch_plain_copy(ha + r * each, shard_ptrs[r], each, copy, shape));
-                    if (e != hipSuccess) return hip_fail(e, "launch zero-copy store");
-                }
-            } else if (contiguous) {
-                if ((st = copy_admit(ctx)) != FCDP_OK) return st;
-                FCDP_HIP(hipMemcpyAsync(h, shard_ptrs[0], flat_bytes, hipMemcpyDeviceToHost, copy), "hipMemcpyAsync(D2H)");
-                if ((st = copy_enqueued(ctx, copy)) != FCDP_OK) return st;
-            } else {
-                for (int32_t r = 0; r < L->G; ++r) {
-                    if ((st = copy_admit(ctx)) != FCDP_OK) return st;
-                    FCDP_HIP(hipMemcpyAsync(h + r * shard_bytes, shard_ptrs[r], shard_bytes, hipMemcpyDeviceToHost, copy), "hipMemcpyAsync(D2H)");
-                    if ((st = copy_enqueued(ctx, copy)) != FCDP_OK) return st;
-                }
-            }
+            if ((st = enqueue_store(L, ctx, shard_ptrs, host_cache, store_alias, store_cache, compute, copy)) != FCDP_OK)
+                return st;
         }
         for (int32_t r = 0; r < L->G; ++r) small[r] = shard_ptrs[r];
         return run_windowed(L->unflatten, tabs->unflatten, fcdp::TensorSide::Dst, L->T, small, L->G,
@@ -441,11 +462,13 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
         if (st != FCDP_OK) return st;
         FCDP_HIP(hipEventRecord(use->done, compute), "hipEventRecord(staging)");
         use->staging = staging;
+        ctx->fetched_bytes += static_cast<int64_t>(flat_bytes);
         return FCDP_OK;
     }
     // zero-copy: the kernel's loads cross the host link
     if ((st = order_after(ctx, copy, compute)) != FCDP_OK) return st;
     for (int32_t r = 0; r < L->G; ++r) small[r] = static_cast<const char *>(zc_alias) + r * shard_bytes;
+    ctx->fetched_bytes += static_cast<int64_t>(L->N) * L->esz;
     return run_windowed(L->unflatten, tabs->unflatten, fcdp::TensorSide::Dst, L->T, small, L->G,
                         reinterpret_cast<const void *const *>(tensor_ptrs), false, 0, compute,
                         "launch zero-copy unflatten", FCDP_KERNEL_UNFLATTEN_ZEROCOPY, tune.link_max_wgs,
@@ -469,6 +492,37 @@ fcdp_status fcdp_flatten_to_shards(const fcdp_layout *L, const void *const *tens
     return run_windowed(L->flatten, tabs->flatten, fcdp::TensorSide::Src, L->T, small, L->G, tensor_ptrs,
                         tune.copy_nt != 0, tune.copy_wg_per_cu, static_cast<hipStream_t>(stream), "launch flatten",
                         FCDP_KERNEL_FLATTEN);
+}
+
+fcdp_status fcdp_cache_store(const fcdp_layout *L, const void *const *shard_ptrs, void *host_cache,
+                             int store_mode, fcdp_stream compute_, fcdp_stream copy_)
+{
+    const char *fn = "fcdp_cache_store";
+    if (!L) return fail(FCDP_EINVAL, std::string(fn) + ": layout is NULL");
+    if (store_mode != FCDP_STORE_DMA && store_mode != FCDP_STORE_ZEROCOPY)
+        return fail(FCDP_EINVAL, std::string(fn) + ": store_mode must be FCDP_STORE_DMA or FCDP_STORE_ZEROCOPY");
+    fcdp_status st = check_shard_ptrs(L, shard_ptrs, fn);
+    if (st != FCDP_OK) return st;
+    if (!host_cache) return fail(FCDP_EINVAL, std::string(fn) + ": host_cache is NULL");
+    if (!aligned16(host_cache)) return fail(FCDP_EALIGN, std::string(fn) + ": host_cache is not 16-byte aligned");
+    if (L->N_pad == 0) return FCDP_OK;
+    void *alias = nullptr;
+    if (store_mode == FCDP_STORE_ZEROCOPY && (st = mapped_alias(host_cache, fn, &alias)) != FCDP_OK) return st;
+    DeviceCtx *ctx = nullptr;
+    if ((st = current_ctx(&ctx)) != FCDP_OK) return st;
+    return enqueue_store(L, ctx, shard_ptrs, host_cache, alias, store_mode,
+                         static_cast<hipStream_t>(compute_), static_cast<hipStream_t>(copy_));
+}
+
+fcdp_status fcdp_link_bytes(int32_t reset, int64_t *stored, int64_t *fetched)
+{
+    DeviceCtx *ctx = nullptr;
+    fcdp_status st = current_ctx(&ctx);
+    if (st != FCDP_OK) return st;
+    if (stored) *stored = ctx->stored_bytes;
+    if (fetched) *fetched = ctx->fetched_bytes;
+    if (reset) ctx->stored_bytes = ctx->fetched_bytes = 0;
+    return FCDP_OK;
 }
 
 fcdp_status fcdp_reduce_grad_shard(const void *const *partial_ptrs, int32_t G, int64_t elem_offset,
@@ -603,7 +657,10 @@ fcdp_status fcdp_host_cache_free(void *host)
 } // extern "C"
 
 struct fcdp_cache_state {
-    std::vector<uint8_t> dirty; // [layer][class]
+    std::vector<uint8_t> dirty;    // [layer][class]
+    std::vector<uint8_t> pending;  // [layer][class]: handed out for storing in this forward pass
+    std::vector<uint8_t> resident; // [layer]: kept on the device until its backward pass
+    double tau = 0.0;
     int32_t L = 0;
 };
 
@@ -618,6 +675,8 @@ fcdp_status fcdp_cache_state_create(int32_t n_layers, fcdp_cache_state **out)
     if (!s) return fail(FCDP_ENOMEM, "fcdp_cache_state_create: out of host memory");
     s->L = n_layers;
     s->dirty.assign(static_cast<size_t>(n_layers) * 2, 1); // Alg. 1: everything starts dirty
+    s->pending.assign(static_cast<size_t>(n_layers) * 2, 0);
+    s->resident.assign(static_cast<size_t>(n_layers), 0);
     *out = s;
     return FCDP_OK;
 }
@@ -638,6 +697,7 @@ fcdp_status fcdp_cache_state_forward_source(fcdp_cache_state *s, int32_t layer, 
         *src = FCDP_SRC_DEVICE_SHARDS; // inter-node gather result, then H <- p
         *store_cache = 1;
         d = 0;
+        s->pending[static_cast<size_t>(layer) * 2 + klass] = 1;
     } else {
         *src = host_mode;
         *store_cache = 0;
@@ -652,6 +712,10 @@ fcdp_status fcdp_cache_state_backward_source(const fcdp_cache_state *s, int32_t 
     if (!s || !src) return fail(FCDP_EINVAL, std::string(fn) + ": NULL argument");
     if (layer < 0 || layer >= s->L || klass < 0 || klass > 1) return fail(FCDP_EINVAL, std::string(fn) + ": layer or class out of range");
     if (!host_mode_ok(host_mode)) return fail(FCDP_EINVAL, std::string(fn) + ": host_mode must be a host source");
+    if (s->resident[layer]) {
+        *src = FCDP_SRC_DEVICE_RESIDENT;
+        return FCDP_OK;
+    }
     if (s->dirty[static_cast<size_t>(layer) * 2 + klass])
         return fail(FCDP_ESTATE, std::string(fn) + ": backward before the forward pass stored this layer");
     *src = host_mode;
@@ -661,7 +725,47 @@ fcdp_status fcdp_cache_state_backward_source(const fcdp_cache_state *s, int32_t 
 fcdp_status fcdp_cache_state_optimizer_step(fcdp_cache_state *s)
 {
     if (!s) return fail(FCDP_EINVAL, "fcdp_cache_state_optimizer_step: NULL state");
-    for (int32_t l = 0; l < s->L; ++l) s->dirty[static_cast<size_t>(l) * 2 + 1] = 1;
+    for (int32_t l = 0; l < s->L; ++l) {
+        s->dirty[static_cast<size_t>(l) * 2 + 1] = 1;
+        s->pending[static_cast<size_t>(l) * 2] = s->pending[static_cast<size_t>(l) * 2 + 1] = 0;
+        s->resident[l] = 0;
+    }
+    return FCDP_OK;
+}
+
+fcdp_status fcdp_cache_state_set_tau(fcdp_cache_state *s, double tau)
+{
+    if (!s) return fail(FCDP_EINVAL, "fcdp_cache_state_set_tau: NULL state");
+    if (!(tau >= 0.0 && tau <= 1.0)) return fail(FCDP_EINVAL, "fcdp_cache_state_set_tau: tau must be in [0, 1]");
+    s->tau = tau;
+    return FCDP_OK;
+}
+
+fcdp_status fcdp_cache_state_place(fcdp_cache_state *s, int32_t layer, int64_t used_bytes,
+                                   int64_t total_bytes, int32_t *keep)
+{
+    const char *fn = "fcdp_cache_state_place";
+    if (!s || !keep) return fail(FCDP_EINVAL, std::string(fn) + ": NULL argument");
+    if (layer < 0 || layer >= s->L) return fail(FCDP_EINVAL, std::string(fn) + ": layer out of range");
+    if (total_bytes <= 0 || used_bytes < 0 || used_bytes > total_bytes)
+        return fail(FCDP_EINVAL, std::string(fn) + ": need 0 <= used_bytes <= total_bytes, total_bytes > 0");
+    const double util = static_cast<double>(used_bytes) / static_cast<double>(total_bytes);
+    const bool k = util < s->tau; // Sec. 4.4: below the threshold the layer stays on the device
+    for (int c = 0; c < 2; ++c) {
+        uint8_t &p = s->pending[static_cast<size_t>(layer) * 2 + c];
+        if (k && p) s->dirty[static_cast<size_t>(layer) * 2 + c] = 1; // not stored after all
+        p = 0;
+    }
+    s->resident[layer] = k ? 1 : 0;
+    *keep = k ? 1 : 0;
+    return FCDP_OK;
+}
+
+fcdp_status fcdp_cache_state_release(fcdp_cache_state *s, int32_t layer)
+{
+    if (!s) return fail(FCDP_EINVAL, "fcdp_cache_state_release: NULL state");
+    if (layer < 0 || layer >= s->L) return fail(FCDP_EINVAL, "fcdp_cache_state_release: layer out of range");
+    s->resident[layer] = 0;
     return FCDP_OK;
 }
 

@@ -285,11 +285,15 @@ __device__ __forceinline__ void store4(char *out, int64_t vec, const float (&a)[
 #define FCDP_REDUCE_UNROLL 4 // 4-element vectors per thread
 #endif
 #ifndef FCDP_REDUCE_NT
-#define FCDP_REDUCE_NT 1     // non-temporal loads and stores
+#define FCDP_REDUCE_NT 1     // non-temporal loads
+#endif
+#ifndef FCDP_REDUCE_NT_STORE
+#define FCDP_REDUCE_NT_STORE 1 // non-temporal stores
 #endif
 constexpr int kGroup = 8;    // partials loaded back to back before their adds
 constexpr int kReduceUnroll = FCDP_REDUCE_UNROLL;
 constexpr bool kReduceNT = FCDP_REDUCE_NT != 0;
+constexpr bool kReduceNTStore = FCDP_REDUCE_NT_STORE != 0;
 
 // Adds partials g0 .. g0+K-1 to acc, strictly in that order.  All K*UNROLL
 // loads are issued before the first add.
@@ -337,7 +341,7 @@ __device__ __forceinline__ void reduce_tile(const ReduceArgs &a, int64_t b0, int
         add_group<REM, IN_F32, ALIGNED, UNROLL, NT>(a, full, lidx, acc);
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u)
-        if (!GUARD || idx[u] < nvec) store4<OUT_F32, NT>(a.out, idx[u], acc[u]);
+        if (!GUARD || idx[u] < nvec) store4<OUT_F32, kReduceNTStore>(a.out, idx[u], acc[u]);
 }
 
 // REM = G mod kGroup is a template parameter, so the rank loop is a counted

@@ -82,3 +82,24 @@ def test_sources_per_phase():
     assert bw == [2, 1, 0]
     # at the end only trainable parameters are dirty
     assert all(d == (k[1] == "lora") for k, d in tr["dirty"].items())
+
+
+def test_adaptive_placement_limits():
+    """Sec. 4.4: tau near 0 forces every layer to host memory (the plain
+    schedule: one store and one load per layer), tau near 100 % keeps
+    everything on the device (no PCIe traffic); in between, fewer bytes move
+    the higher tau is."""
+    sizes = [100, 200, 300, 400, 500]
+    W = sum(sizes)
+
+    def util(it, l):                 # activations pile up through the forward pass
+        return 0.30 + 0.12 * l
+
+    low = alg1.replay_adaptive(sizes, util, 0.0, 2)["iterations"]
+    assert all(r == {"kept": [], "stored": W, "fetched": W} for r in low)
+    high = alg1.replay_adaptive(sizes, util, 1.0, 2)["iterations"]
+    assert all(r == {"kept": [0, 1, 2, 3, 4], "stored": 0, "fetched": 0} for r in high)
+    mid = alg1.replay_adaptive(sizes, util, 0.55, 1)["iterations"][0]
+    assert mid["kept"] == [0, 1, 2] and mid["stored"] == 900 and mid["fetched"] == 900
+    moved = [alg1.replay_adaptive(sizes, util, t / 20, 1)["iterations"][0]["stored"] for t in range(21)]
+    assert moved == sorted(moved, reverse=True) and moved[0] == W and moved[-1] == 0

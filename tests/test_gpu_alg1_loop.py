@@ -107,3 +107,66 @@ def test_training_loop_cache_coherence(peft, host_mode):
         assert set(kinds) == {"miss"}
     for H in caches:
         H.free()
+
+
+@pytest.mark.parametrize("tau", [0.0, 0.5, 1.0])
+def test_adaptive_gpu_caching(tau):
+    """Sec. 4.4: layers whose utilisation at the 'cache on CPU' point is below
+    tau stay on the device (no store, no fetch); the others take the host
+    cache.  Either way the backward pass sees the layer's parameters, and the
+    bytes over the host link are the oracle's."""
+    from oracle import alg1
+    nl, G = 5, 4
+    L = fcdp.fcdp_layout_build(SIZES, None, G, 2)
+    L.prepare()
+    Np, S = L.padded_numel, L.shard_numel
+    g = synth.rng(0, 777, synth.KIND_MISC)
+    params = [[g.integers(0, 65536, size=k, dtype=np.uint16) for k in SIZES] for _ in range(nl)]
+    caches = [fcdp.fcdp_host_cache_alloc(Np * 2) for _ in range(nl)]
+    state = fcdp.CacheState(nl)
+    state.set_tau(tau)
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    staging = [torch.zeros(Np * 2, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    # one tensor set per layer: a kept layer's tensors must survive until its backward pass
+    outs = [[torch.zeros(k * 2, dtype=torch.uint8, device="cuda") for k in SIZES] for _ in range(nl)]
+
+    def util(it, l):
+        return 0.2 + 0.15 * l
+
+    want = alg1.replay_adaptive([Np * 2] * nl, util, tau, 2)["iterations"]
+    total = 288 << 30
+    for it in range(2):
+        fcdp.fcdp_link_bytes(True)
+        gathered = []
+        for l in range(nl):
+            src, store = state.forward_source(l, 1, fcdp.SRC_HOST_DMA)
+            assert src == fcdp.SRC_DEVICE_SHARDS
+            flat = oracle.flatten(params[l], G)
+            gathered.append(to_dev(flat))
+            ptrs = [gathered[l].data_ptr() + r * S * 2 for r in range(G)]
+            torch.cuda.synchronize()
+            fcdp.fcdp_materialize_layer(L, src, ptrs, None, None, outs[l], fcdp.STORE_NONE, compute, copy)
+            # ... the layer's forward computation would run here ...
+            if not state.place(l, int(util(it, l) * total), total):
+                fcdp.fcdp_cache_store(L, ptrs, caches[l], fcdp.STORE_DMA, compute, copy)
+        torch.cuda.synchronize()
+        for l in range(nl - 1, -1, -1):
+            src = state.backward_source(l, 1, fcdp.SRC_HOST_DMA)
+            if src != fcdp.SRC_DEVICE_RESIDENT:
+                for o in outs[l]:
+                    o.zero_()           # an offloaded layer was freed after its forward pass
+                torch.cuda.synchronize()
+            fcdp.fcdp_materialize_layer(L, src, None, caches[l], staging[l % 2], outs[l],
+                                        fcdp.STORE_NONE, compute, copy)
+            torch.cuda.synchronize()
+            for t, k in enumerate(SIZES):
+                assert np.array_equal(_bits(outs[l][t]), params[l][t]), (tau, it, l, t)
+            assert (src == fcdp.SRC_DEVICE_RESIDENT) == (l in want[it]["kept"])
+            state.release(l)
+        stored, fetched = fcdp.fcdp_link_bytes()
+        assert (stored, fetched) == (want[it]["stored"], want[it]["fetched"])
+        for l in range(nl):
+            params[l] = [g.integers(0, 65536, size=k, dtype=np.uint16) for k in SIZES]
+        state.optimizer_step()
+    for H in caches:
+        H.free()

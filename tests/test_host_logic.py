@@ -289,3 +289,55 @@ def test_no_gpu_means_loud_failure():
     with pytest.raises(fcdp.FcdpError) as e:
         fcdp.fcdp_materialize_layer(L, fcdp.SRC_DEVICE_SHARDS, [0x1000, 0x2000], None, None, [0x8000])
     assert e.value.name in ("FCDP_EHIP", "FCDP_ENOMEM")
+
+
+def test_adaptive_placement_follows_the_oracle():
+    """The library's keep/offload decisions, residency and dirty flags against
+    the Sec. 4.4 replay (full fine-tuning, utilisation rising with depth)."""
+    nl = 6
+    sizes = [1000 + 10 * l for l in range(nl)]
+
+    def util(it, l):
+        return min(0.95, 0.25 + 0.1 * l + 0.05 * it)
+
+    for tau in (0.0, 0.4, 0.62, 1.0):
+        st = fcdp.CacheState(nl)
+        st.set_tau(tau)
+        want = alg1.replay_adaptive(sizes, util, tau, 3)["iterations"]
+        for it in range(3):
+            kept, stored, fetched = [], 0, 0
+            for l in range(nl):
+                src, store = st.forward_source(l, 1, fcdp.SRC_HOST_DMA)
+                assert src == fcdp.SRC_DEVICE_SHARDS and store      # every forward is a miss
+                total = 1 << 30
+                if st.place(l, int(util(it, l) * total), total):
+                    kept.append(l)
+                    assert st.is_dirty(l, 1) == 1       # the host copy was not refreshed
+                else:
+                    stored += sizes[l]
+                    assert st.is_dirty(l, 1) == 0
+            for l in range(nl - 1, -1, -1):
+                src = st.backward_source(l, 1, fcdp.SRC_HOST_DMA)
+                if l in kept:
+                    assert src == fcdp.SRC_DEVICE_RESIDENT
+                else:
+                    assert src == fcdp.SRC_HOST_DMA
+                    fetched += sizes[l]
+                st.release(l)
+            assert {"kept": kept, "stored": stored, "fetched": fetched} == want[it]
+            st.optimizer_step()
+    st = fcdp.CacheState(2)
+    with pytest.raises(fcdp.FcdpError):
+        st.set_tau(1.5)
+    with pytest.raises(fcdp.FcdpError):
+        st.place(0, 10, 0)
+    with pytest.raises(fcdp.FcdpError):
+        st.place(5, 1, 10)
+    # a released layer that was never stored cannot be served in a backward pass
+    st.set_tau(1.0)
+    st.forward_source(0, 1, fcdp.SRC_HOST_DMA)
+    assert st.place(0, 1, 10)
+    st.release(0)
+    with pytest.raises(fcdp.FcdpError) as e:
+        st.backward_source(0, 1, fcdp.SRC_HOST_DMA)
+    assert e.value.name == "FCDP_ESTATE"
