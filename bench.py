@@ -265,6 +265,23 @@ def main():
     unpack_us = 1e3 * time_kernel(lambda: fcdp.fcdp_unpack_trainable(play, ppacked, pflat, compute), reps=50)
     pred_us = 1e3 * time_kernel(lambda: fcdp.fcdp_reduce_grad_shard(
         pg_ptrs, pcfg.G, 0, pS, fcdp.F32, fcdp.F32, pshard, compute), reps=50)
+    # the same from G unpacked flat gradients: G packs + one reduce, against the fused launch
+    # (all G flat gradients alias one buffer here: only the launch pattern is timed)
+    pflatg = torch.zeros(play.padded_numel, dtype=torch.float32, device=dev).normal_(0, 1e-3)
+    ppk = torch.zeros(play.packed_numel, dtype=torch.float32, device=dev)
+    play4 = fcdp.fcdp_layout_build(pcfg.numel, pcfg.trainable, pcfg.G, 4)
+    play4.prepare()
+    fg_ptrs = fcdp.pointer_array([pflatg] * pcfg.G)
+    torch.cuda.synchronize()
+
+    def unfused():
+        for _ in range(pcfg.G):
+            fcdp.fcdp_pack_trainable(play4, pflatg, ppk, compute)
+        fcdp.fcdp_reduce_grad_shard(pg_ptrs, pcfg.G, 0, pS, fcdp.F32, fcdp.F32, pshard, compute)
+
+    unfused_us = 1e3 * time_kernel(unfused, reps=30)
+    fused_us = 1e3 * time_kernel(lambda: fcdp.fcdp_reduce_trainable_shard(
+        play4, fg_ptrs, 0, fcdp.F32, fcdp.F32, pshard, compute), reps=50)
 
     # ---- CPU oracle on a bounded sample of the same workload -------------
     cpu = None
@@ -331,6 +348,8 @@ def main():
                      "fetched_bytes_per_step": link_fetched // args.steps},
         "peft": {"workload": "llama7b_lora_g8 (LoRA r16 on q,v): per layer", "pack_us": round(pack_us, 2),
                  "unpack_us": round(unpack_us, 2), "reduce_packed_us": round(pred_us, 2),
+                 "grad_shard_from_flat_grads_us": {"G_packs_then_reduce": round(unfused_us, 2),
+                                                   "fused_reduce_trainable_shard": round(fused_us, 2)},
                  "trainable_bytes": play.trainable_numel * 2},
         "cpu_baseline": cpu,
     }

@@ -212,6 +212,26 @@ fcdp_status fcdp_reduce_grad_shard(const void *const *partial_ptrs, int32_t G,
                                    fcdp_dtype in, fcdp_dtype out,
                                    void *out_shard, fcdp_stream stream);
 
+/* Gradient-shard sum of the trainable parameters straight from G unpacked
+ * flat gradients: pack and reduce in one launch (Alg. 1 "ReduceScatter(grad
+ * W_t)"; Sec. 4.5: only trainable parameters take part).  With Sp =
+ * packed_numel / G and pk(.) the packed order of fcdp_pack_trainable,
+ *     out[k] = sum over g = 0..G-1, in that order, of grad_g[flat index of
+ *              packed element rank*Sp + k],     k in [0, Sp)
+ * under the arithmetic of fcdp_reduce_grad_shard; packed positions beyond
+ * N_t (the zero tail) give +0.
+ *   flat_grad_ptrs  host array of G dev ptrs (G = the layout's G), each a
+ *                   flat gradient of N_pad elements of dtype `in`
+ *   rank            which shard of the packed buffer to produce, 0..G-1
+ *   out_shard       dev ptr, Sp elements of dtype `out`; must not overlap
+ *                   any input
+ */
+fcdp_status fcdp_reduce_trainable_shard(const fcdp_layout *layout,
+                                        const void *const *flat_grad_ptrs,
+                                        int32_t rank, fcdp_dtype in,
+                                        fcdp_dtype out, void *out_shard,
+                                        fcdp_stream stream);
+
 /* --------------------------------------------------- PEFT pack and unpack
  * Under PEFT only trainable parameters cross the node boundary (Sec. 4.5,
  * Alg. 1's dirty branch and its reduce-scatter of grad W_t).
@@ -320,7 +340,8 @@ typedef enum {
     FCDP_KERNEL_PACK = 4,
     FCDP_KERNEL_UNPACK = 5,
     FCDP_KERNEL_STORE_ZEROCOPY = 6,
-    FCDP_KERNEL_PROBE_COPY = 7
+    FCDP_KERNEL_PROBE_COPY = 7,
+    FCDP_KERNEL_REDUCE_TRAINABLE = 8
 } fcdp_kernel_kind;
 fcdp_status fcdp_timing_enable(int32_t capacity);
 fcdp_status fcdp_timing_collect(int32_t kind, int64_t *launches, double *total_ms);

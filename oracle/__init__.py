@@ -249,3 +249,17 @@ def unpack(packed: np.ndarray, flat: np.ndarray, numel: Sequence[int],
     _check(lib().fcdp_oracle_unpack(
         _p(_c(packed)), _p(n), _p(tr), ctypes.c_int32(len(n)),
         ctypes.c_int32(flat.dtype.itemsize), _p(_c(flat))), "unpack")
+
+
+def reduce_trainable(flat_partials: Sequence[np.ndarray], numel: Sequence[int],
+                     trainable: Sequence[int], G: int, rank: int,
+                     out_dtype: int, q: int = 64) -> np.ndarray:
+    """This rank's shard of the summed trainable gradients.
+
+    The composition of two definitions above: every rank's flat gradient is
+    packed (trainable ranges in tensor order, zero tail), then the packed
+    buffers are summed in rank order over this rank's slice.
+    """
+    packed = [pack(p, numel, trainable, G, q) for p in flat_partials]
+    Sp = packed[0].size // G
+    return reduce(packed, rank * Sp, Sp, out_dtype)

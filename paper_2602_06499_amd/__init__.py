@@ -10,10 +10,10 @@ from .binding import (  # noqa: F401
     STORE_NONE, STORE_DMA, STORE_ZEROCOPY,
     FcdpError, Layout, CacheState, HostCache,
     fcdp_layout_build, fcdp_materialize_layer, fcdp_flatten_to_shards,
-    fcdp_reduce_grad_shard, fcdp_pack_trainable, fcdp_unpack_trainable,
+    fcdp_reduce_grad_shard, fcdp_reduce_trainable_shard, fcdp_pack_trainable, fcdp_unpack_trainable,
     fcdp_host_cache_alloc, fcdp_host_cache_free, fcdp_tuning_set,
     fcdp_tuning_get, fcdp_probe_copy, fcdp_last_error, load_library,
     library_path, pointer_array, fcdp_timing_enable, fcdp_timing_collect,
     KERNEL_UNFLATTEN, KERNEL_UNFLATTEN_ZEROCOPY, KERNEL_FLATTEN, KERNEL_REDUCE,
-    KERNEL_PACK, KERNEL_UNPACK, KERNEL_STORE_ZEROCOPY, KERNEL_PROBE_COPY,
+    KERNEL_PACK, KERNEL_UNPACK, KERNEL_STORE_ZEROCOPY, KERNEL_PROBE_COPY, KERNEL_REDUCE_TRAINABLE,
 )

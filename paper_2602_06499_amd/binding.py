@@ -40,7 +40,8 @@ EXPORTS = [
     "fcdp_layout_offsets", "fcdp_layout_segments", "fcdp_layout_copy_plan",
     "fcdp_layout_prepare",
     "fcdp_materialize_layer", "fcdp_cache_store", "fcdp_flatten_to_shards",
-    "fcdp_reduce_grad_shard", "fcdp_pack_trainable", "fcdp_unpack_trainable",
+    "fcdp_reduce_grad_shard", "fcdp_reduce_trainable_shard",
+    "fcdp_pack_trainable", "fcdp_unpack_trainable",
     "fcdp_host_cache_alloc", "fcdp_host_cache_free",
     "fcdp_cache_state_create", "fcdp_cache_state_destroy",
     "fcdp_cache_state_forward_source", "fcdp_cache_state_backward_source",
@@ -103,6 +104,7 @@ def load_library() -> ctypes.CDLL:
     lib.fcdp_cache_state_release.argtypes = [vp, i32]
     lib.fcdp_link_bytes.argtypes = [i32, c.POINTER(i64), c.POINTER(i64)]
     lib.fcdp_reduce_grad_shard.argtypes = [vp, i32, i64, i64, c.c_int, c.c_int, vp, vp]
+    lib.fcdp_reduce_trainable_shard.argtypes = [vp, vp, i32, c.c_int, c.c_int, vp, vp]
     lib.fcdp_pack_trainable.argtypes = [vp, vp, vp, vp]
     lib.fcdp_unpack_trainable.argtypes = [vp, vp, vp, vp]
     lib.fcdp_host_cache_alloc.argtypes = [c.c_size_t, c.c_int, c.POINTER(vp), c.POINTER(vp)]
@@ -273,6 +275,14 @@ def fcdp_reduce_grad_shard(partial_ptrs, G: int, elem_offset: int, count: int,
         _ptr(out_shard), _stream(stream)))
 
 
+def fcdp_reduce_trainable_shard(layout: Layout, flat_grad_ptrs, rank: int,
+                                in_dtype: int, out_dtype: int, out_shard,
+                                stream=None) -> None:
+    _check(load_library().fcdp_reduce_trainable_shard(
+        layout.handle, _ptr_array(flat_grad_ptrs), rank, in_dtype, out_dtype,
+        _ptr(out_shard), _stream(stream)))
+
+
 def fcdp_pack_trainable(layout: Layout, flat, packed, stream=None) -> None:
     _check(load_library().fcdp_pack_trainable(
         layout.handle, _ptr(flat), _ptr(packed), _stream(stream)))
@@ -388,6 +398,7 @@ KERNEL_PACK = 4
 KERNEL_UNPACK = 5
 KERNEL_STORE_ZEROCOPY = 6
 KERNEL_PROBE_COPY = 7
+KERNEL_REDUCE_TRAINABLE = 8
 
 
 def fcdp_timing_enable(capacity: int) -> None:

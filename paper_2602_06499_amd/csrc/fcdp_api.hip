@@ -556,6 +556,56 @@ fcdp_status fcdp_reduce_grad_shard(const void *const *partial_ptrs, int32_t G, i
     return FCDP_OK;
 }
 
+fcdp_status fcdp_reduce_trainable_shard(const fcdp_layout *L, const void *const *flat_grad_ptrs,
+                                        int32_t rank, fcdp_dtype in, fcdp_dtype out, void *out_shard,
+                                        fcdp_stream stream)
+{
+    const char *fn = "fcdp_reduce_trainable_shard";
+    if (!L) return fail(FCDP_EINVAL, std::string(fn) + ": layout is NULL");
+    if (!flat_grad_ptrs) return fail(FCDP_EINVAL, std::string(fn) + ": flat_grad_ptrs is NULL");
+    if (rank < 0 || rank >= L->G) return fail(FCDP_EINVAL, std::string(fn) + ": rank out of range");
+    if ((in != FCDP_BF16 && in != FCDP_F32) || (out != FCDP_BF16 && out != FCDP_F32))
+        return fail(FCDP_EINVAL, std::string(fn) + ": unknown dtype");
+    if (!out_shard) return fail(FCDP_EINVAL, std::string(fn) + ": out_shard is NULL");
+    if (!aligned16(out_shard)) return fail(FCDP_EALIGN, std::string(fn) + ": out_shard is not 16-byte aligned");
+    const int64_t ie = in == FCDP_F32 ? 4 : 2, oe = out == FCDP_F32 ? 4 : 2;
+    const int64_t Sp = L->N_packed / L->G;
+    const char *ob = static_cast<const char *>(out_shard);
+    for (int32_t g = 0; g < L->G; ++g) {
+        if (!flat_grad_ptrs[g]) return fail(FCDP_EINVAL, std::string(fn) + ": a gradient pointer is NULL");
+        if (!aligned16(flat_grad_ptrs[g])) return fail(FCDP_EALIGN, std::string(fn) + ": a gradient pointer is not 16-byte aligned");
+        const char *pb = static_cast<const char *>(flat_grad_ptrs[g]);
+        if (Sp > 0 && pb < ob + Sp * oe && ob < pb + L->N_pad * ie)
+            return fail(FCDP_EINVAL, std::string(fn) + ": out_shard overlaps an input");
+    }
+    if (Sp == 0) return FCDP_OK;
+    // this rank's slice [lo, hi) of the packed order, cut by the trainable runs
+    const int64_t lo = static_cast<int64_t>(rank) * Sp, hi = lo + Sp;
+    std::vector<fcdp::ReduceRuns> batches(1);
+    auto add = [&](int64_t src, int64_t dst, int64_t count) {
+        if (batches.back().n_runs == fcdp::kMaxReduceRuns) batches.emplace_back();
+        fcdp::ReduceRuns &b = batches.back();
+        b.src_off[b.n_runs] = src;
+        b.dst_off[b.n_runs] = dst;
+        b.count[b.n_runs] = count;
+        ++b.n_runs;
+    };
+    int64_t c = 0; // packed position of the current tensor
+    for (int32_t t = 0; t < L->T; ++t) {
+        if (!L->trainable[t]) continue;
+        const int64_t a = std::max(c, lo), b = std::min(c + L->numel[t], hi);
+        if (b > a) add(L->off[t] + (a - c), a - lo, b - a);
+        c += L->numel[t];
+    }
+    if (hi > std::max(lo, L->N_t)) add(-1, std::max(lo, L->N_t) - lo, hi - std::max(lo, L->N_t)); // zero tail
+    for (const fcdp::ReduceRuns &b : batches) {
+        hipError_t e = static_cast<hipError_t>(fcdp::launch_reduce_runs(
+            flat_grad_ptrs, L->G, b, in, out, out_shard, stream, timing_events(FCDP_KERNEL_REDUCE_TRAINABLE)));
+        if (e != hipSuccess) return hip_fail(e, "launch trainable reduce");
+    }
+    return FCDP_OK;
+}
+
 static fcdp_status pack_or_unpack(const fcdp_layout *L, const void *src, void *dst, bool pack,
                                   fcdp_stream stream, const char *fn)
 {

@@ -134,6 +134,19 @@ struct PlainCopy {
     int nt = -1;                                           // -1 = copy_nt
     LaunchEvents ev;
 };
+// Rank-order reduction over a few runs: run k sums `count[k]` elements that
+// start at element src_off[k] of every partial into out + dst_off[k]; a run
+// with src_off < 0 writes zeros.
+constexpr int kMaxReduceRuns = 32;
+struct ReduceRuns {
+    int32_t n_runs = 0;
+    int64_t src_off[kMaxReduceRuns];
+    int64_t dst_off[kMaxReduceRuns];
+    int64_t count[kMaxReduceRuns];
+};
+int launch_reduce_runs(const void *const *partials, int32_t G, const ReduceRuns &runs,
+                       int in_dtype, int out_dtype, void *out, void *stream,
+                       const LaunchEvents &ev = LaunchEvents());
 int launch_plain_copy(void *dst, const void *src, size_t bytes, void *stream,
                       const PlainCopy &shape = PlainCopy());
 int device_cu_count();

@@ -382,6 +382,93 @@ __global__ void __launch_bounds__(256) reduce_ranks(const ReduceArgs a)
     }
 }
 
+// ---- reduce over runs (trainable ranges of unpacked gradients) ------------
+constexpr int kRunPieceElems = 2048; // elements one workgroup reduces
+
+struct ReduceRunArgs {
+    int32_t first_piece[kMaxReduceRuns + 1]; // prefix sums; unused = INT32_MAX
+    int32_t G;
+    int32_t reserved;
+    int64_t src_off[kMaxReduceRuns]; // elements; < 0: the run is zeros
+    int64_t dst_off[kMaxReduceRuns];
+    int64_t count[kMaxReduceRuns];
+    const char *p[FCDP_MAX_G];
+    char *out;
+};
+
+template <bool IN_F32>
+__device__ __forceinline__ float load_elem(const char *base, int64_t e)
+{
+    if constexpr (IN_F32)
+        return reinterpret_cast<const float *>(base)[e];
+    else
+        return __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t *>(base)[e]) << 16);
+}
+
+template <bool OUT_F32>
+__device__ __forceinline__ void store_elem(char *base, int64_t e, float v)
+{
+    if constexpr (OUT_F32)
+        reinterpret_cast<float *>(base)[e] = v;
+    else
+        reinterpret_cast<uint16_t *>(base)[e] = static_cast<uint16_t>(bf16_rne_bits(v));
+}
+
+// Workgroup i reduces piece i: up to kRunPieceElems elements of one run.  The
+// run is found from the block index by counting prefix sums held in the
+// kernel argument.  Element offsets are arbitrary, so loads use
+// element-aligned vectors and stores fall back to single elements when the
+// destination is not vector aligned.  Same arithmetic and order as
+// reduce_ranks.
+template <bool IN_F32, bool OUT_F32>
+__global__ void __launch_bounds__(256) reduce_runs(const ReduceRunArgs a)
+{
+    const int32_t total = a.first_piece[kMaxReduceRuns];
+    for (int32_t i = blockIdx.x; i < total; i += gridDim.x) {
+        int32_t r = 0;
+#pragma unroll
+        for (int k = 1; k < kMaxReduceRuns; ++k) r += (i >= a.first_piece[k]) ? 1 : 0;
+        const int64_t e0 = static_cast<int64_t>(i - a.first_piece[r]) * kRunPieceElems;
+        int64_t n = a.count[r] - e0;
+        if (n > kRunPieceElems) n = kRunPieceElems;
+        const int64_t so = a.src_off[r];
+        const int64_t s = so + e0, d = a.dst_off[r] + e0;
+        constexpr int64_t oes = OUT_F32 ? 4 : 2;
+        const bool vec_store = ((reinterpret_cast<uintptr_t>(a.out) + d * oes) & (OUT_F32 ? 15 : 7)) == 0;
+        const int64_t nvec = n >> 2;
+        for (int64_t v = threadIdx.x; v < nvec; v += blockDim.x) {
+            float acc[4] = {-0.0f, -0.0f, -0.0f, -0.0f};
+            if (so >= 0) {
+                for (int g = 0; g < a.G; ++g) {
+                    float x[4];
+                    load4<IN_F32, false, false>(a.p[g] + s * (IN_F32 ? 4 : 2), v, x);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) acc[c] = acc[c] + x[c];
+                }
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[c] = 0.0f;
+            }
+            if (vec_store) {
+                store4<OUT_F32, false>(a.out + d * oes, v, acc);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) store_elem<OUT_F32>(a.out, d + v * 4 + c, acc[c]);
+            }
+        }
+        const int64_t k = (nvec << 2) + threadIdx.x;
+        if (k < n) {
+            float acc = -0.0f;
+            if (so >= 0) {
+                for (int g = 0; g < a.G; ++g) acc = acc + load_elem<IN_F32>(a.p[g], s + k);
+            } else {
+                acc = 0.0f;
+            }
+            store_elem<OUT_F32>(a.out, d + k, acc);
+        }
+    }
+}
+
 int g_cu_count[kMaxDevices] = {0};
 
 // Launches `kernel`; with timing events the dispatch itself carries them.
@@ -501,6 +588,42 @@ int launch_copy(const CopyLaunch &c, void *stream)
     if (unroll >= 4) return launch_copy_h<4>(args, g, b, hint, st, c.ev);
     if (unroll >= 2) return launch_copy_h<2>(args, g, b, hint, st, c.ev);
     return launch_copy_h<1>(args, g, b, hint, st, c.ev);
+}
+
+int launch_reduce_runs(const void *const *partials, int32_t G, const ReduceRuns &runs,
+                       int in_dtype, int out_dtype, void *out, void *stream,
+                       const LaunchEvents &ev)
+{
+    if (runs.n_runs <= 0) return hipSuccess;
+    ReduceRunArgs args;
+    int64_t total = 0;
+    for (int k = 0; k < kMaxReduceRuns; ++k) {
+        if (k < runs.n_runs) {
+            args.first_piece[k] = static_cast<int32_t>(total);
+            args.src_off[k] = runs.src_off[k];
+            args.dst_off[k] = runs.dst_off[k];
+            args.count[k] = runs.count[k];
+            total += (runs.count[k] + kRunPieceElems - 1) / kRunPieceElems;
+        } else {
+            args.first_piece[k] = 0x7fffffff;
+            args.src_off[k] = args.dst_off[k] = args.count[k] = 0;
+        }
+    }
+    if (total <= 0) return hipSuccess;
+    if (total >= 0x7fffffff) return hipErrorInvalidValue;
+    args.first_piece[kMaxReduceRuns] = static_cast<int32_t>(total);
+    args.G = G;
+    args.reserved = 0;
+    for (int g = 0; g < FCDP_MAX_G; ++g)
+        args.p[g] = g < G ? static_cast<const char *>(partials[g]) : nullptr;
+    args.out = static_cast<char *>(out);
+    const dim3 grid(static_cast<unsigned>(total)), block(256);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool inf = in_dtype == FCDP_F32, outf = out_dtype == FCDP_F32;
+    if (inf && outf) return launch_one(reduce_runs<true, true>, grid, block, st, ev, args);
+    if (inf && !outf) return launch_one(reduce_runs<true, false>, grid, block, st, ev, args);
+    if (!inf && outf) return launch_one(reduce_runs<false, true>, grid, block, st, ev, args);
+    return launch_one(reduce_runs<false, false>, grid, block, st, ev, args);
 }
 
 int launch_plain_copy(void *dst, const void *src, size_t bytes, void *stream,

@@ -437,3 +437,47 @@ def test_kernel_timing_hooks():
     finally:
         fcdp.fcdp_timing_enable(0)
     assert torch.equal(x, y) and float(out[0]) == 3.0
+
+
+TRAINABLE_REDUCE_CASES = [
+    ("lora_like", [4096, 160, 160, 4096, 160, 160, 9000, 64], [0, 1, 1, 0, 1, 1, 0, 0], 8, oracle.F32, oracle.F32),
+    ("odd", [1001, 3, 777, 0, 12345, 1], [1, 0, 1, 1, 0, 1], 3, oracle.F32, oracle.F32),
+    ("odd_bf16_out", [1001, 3, 777, 0, 12345, 1], [1, 0, 1, 1, 0, 1], 3, oracle.F32, oracle.BF16),
+    ("bf16_in", [333, 5001, 77, 2050], [0, 1, 1, 1], 4, oracle.BF16, oracle.F32),
+    ("bf16_in_out", [333, 5001, 77, 2050], [1, 1, 0, 1], 2, oracle.BF16, oracle.BF16),
+    ("big_runs", [200000, 70000, 300001, 65536], [1, 0, 1, 1], 5, oracle.F32, oracle.F32),
+    ("none_trainable", [500, 700], [0, 0], 4, oracle.F32, oracle.F32),
+    ("all_trainable_one_rank", [500, 700, 9], [1, 1, 1], 1, oracle.F32, oracle.BF16),
+    ("many_runs", [(37 * i) % 90 + 1 for i in range(150)], [i % 2 for i in range(150)], 2, oracle.F32, oracle.F32),
+]
+
+
+@pytest.mark.parametrize("name,sizes,tr,G,in_dt,out_dt", TRAINABLE_REDUCE_CASES,
+                         ids=[c[0] for c in TRAINABLE_REDUCE_CASES])
+def test_reduce_trainable_shard_parity(name, sizes, tr, G, in_dt, out_dt):
+    """Pack and reduce in one launch, for every rank, against the oracle's
+    pack followed by its rank-order reduce."""
+    L = fcdp.fcdp_layout_build(sizes, tr, G, 2)
+    Np = L.padded_numel
+    g = synth.rng(0, 1200 + G, synth.KIND_GRAD, len(sizes))
+    parts = []
+    for r in range(G):
+        x = g.standard_normal(Np, dtype=np.float32) * np.float32(10.0 ** int(g.integers(-4, 2)))
+        parts.append(x if in_dt == oracle.F32 else synth.to_bf16_bits(x))
+    ies = 4 if in_dt == oracle.F32 else 2
+    oes = 4 if out_dt == oracle.F32 else 2
+    arena = Arena([Np * ies] * G)
+    for r in range(G):
+        arena.fill(r, parts[r])
+    Sp = L.packed_numel // G
+    for rank in range(G):
+        # the oracle packs each rank's gradient, then sums the packed slices
+        want = oracle.reduce_trainable(parts, sizes, tr, G, rank, out_dt)
+        assert want.size == Sp
+        out = Arena([Sp * oes])
+        fcdp.fcdp_reduce_trainable_shard(L, arena.ptrs(), rank, in_dt, out_dt, out.ptr(0), None)
+        torch.cuda.synchronize()
+        got = out.get(0, np.float32 if out_dt == oracle.F32 else np.uint16)
+        _cmp_reduce(got, want, out_dt)
+        out.check_guards()
+    arena.check_guards()
