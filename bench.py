@@ -46,7 +46,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="llama7b_g8")
     ap.add_argument("--layers", type=int, default=0, help="0 = the config's layer count")
-    ap.add_argument("--fetch", choices=["dma", "zerocopy"], default="dma")
+    ap.add_argument("--fetch", choices=["dma", "zerocopy", "scatter"], default="dma")
     ap.add_argument("--store", choices=["dma", "zerocopy"], default="dma")
     ap.add_argument("--tau", type=float, default=0.0,
                     help="adaptive GPU caching threshold (Sec. 4.4); 0 = offload every layer")
@@ -125,7 +125,8 @@ def main():
         cache.numpy(np.uint8)[:] = 0        # touch every page before timing
     log("pinned host cache: %.2f GB allocated and touched in %.1f s" % (layer_bytes * L / 1e9, time.time() - t0))
     compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
-    host_mode = fcdp.SRC_HOST_DMA if args.fetch == "dma" else fcdp.SRC_HOST_ZEROCOPY
+    host_mode = {"dma": fcdp.SRC_HOST_DMA, "zerocopy": fcdp.SRC_HOST_ZEROCOPY,
+                 "scatter": fcdp.SRC_HOST_SCATTER_DMA}[args.fetch]
     store_mode = fcdp.STORE_DMA if args.store == "dma" else fcdp.STORE_ZEROCOPY
     shard_ptrs = [fcdp.pointer_array([w.data_ptr() + r * S * 2 for r in range(G)]) for w in gathered]
     part_ptrs = [fcdp.pointer_array([p.data_ptr() + r * S * 4 for r in range(G)]) for p in partials]
@@ -246,6 +247,8 @@ def main():
         lay, fcdp.SRC_HOST_ZEROCOPY, None, cache.host, None, tensors, False, compute, copy), reps=3)
     dma_ms = time_kernel(lambda: fcdp.fcdp_materialize_layer(
         lay, fcdp.SRC_HOST_DMA, None, cache.host, staging[0], tensors, False, compute, copy), reps=3)
+    sc_ms = time_kernel(lambda: fcdp.fcdp_materialize_layer(
+        lay, fcdp.SRC_HOST_SCATTER_DMA, None, cache.host, None, tensors, False, compute, copy), reps=3)
     bshard = torch.empty(S, dtype=torch.bfloat16, device=dev)
     k3b_ms = time_kernel(lambda: fcdp.fcdp_reduce_grad_shard(
         part_ptrs[0], G, 0, S, fcdp.F32, fcdp.BF16, bshard, compute))
@@ -341,6 +344,7 @@ def main():
                       "probe_h2d": round(link["h2d"], 2), "probe_d2h": round(link["d2h"], 2),
                       "one_layer_dma_fetch_plus_unflatten_ms": round(dma_ms, 3),
                       "one_layer_zero_copy_ms": round(zc_ms, 3),
+                      "one_layer_scatter_dma_ms": round(sc_ms, 3),
                       "zero_copy_gbps": round(N * 2 / (zc_ms * 1e-3) / 1e9, 2)},
         "plain_copy_gbps": round(4 * N / (copy_ms * 1e-3) / 1e9, 1),
         "adaptive": {"tau": args.tau, "kept_layers": len(kept_sets),

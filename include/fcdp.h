@@ -39,6 +39,9 @@
  *     fails an argument check has no side effect.  fcdp_last_error() gives a
  *     thread-local text for the last failing call on the calling thread.
  *   - Zero-element tensors, N = 0 and N_t = 0 are legal no-ops.
+ *   - Threads: a layout is immutable and may be shared.  Data calls may come
+ *     from several threads, but calls that share a staging buffer, a cache
+ *     state object or the timing pool must be serialised by the caller.
  */
 #ifndef FCDP_H
 #define FCDP_H
@@ -71,7 +74,8 @@ typedef enum {
     FCDP_SRC_DEVICE_SHARDS = 0, /* cache miss: scatter the G gathered shards */
     FCDP_SRC_HOST_DMA = 1,      /* cache hit: DMA host cache -> staging, scatter */
     FCDP_SRC_HOST_ZEROCOPY = 2, /* cache hit: kernel reads the mapped host cache */
-    FCDP_SRC_DEVICE_RESIDENT = 3 /* kept on the device since the forward pass: nothing to do */
+    FCDP_SRC_DEVICE_RESIDENT = 3, /* kept on the device since the forward pass: nothing to do */
+    FCDP_SRC_HOST_SCATTER_DMA = 4 /* cache hit: one DMA copy per tensor, no kernel, no staging */
 } fcdp_source;
 
 /* store_cache argument of fcdp_materialize_layer */
@@ -149,6 +153,12 @@ fcdp_status fcdp_layout_prepare(const fcdp_layout *layout);
  * remembers the last scatter that read each staging buffer and makes the
  * next copy into that buffer wait for it, so alternating two staging
  * buffers overlaps the fetch of one layer with the scatter of another.
+ *
+ * FCDP_SRC_HOST_SCATTER_DMA: every tensor is contiguous in the cached flat
+ * image, so T copies on `copy` move host_cache[off_t .. off_t + n_t) straight
+ * into tensor t; no staging buffer and no kernel.  The copies wait for what
+ * is enqueued on `compute` before the call (earlier readers of the tensors),
+ * and `compute` waits for the copies.
  *
  * FCDP_SRC_HOST_ZEROCOPY: one kernel on `compute` reads host_cache through
  * its device mapping and writes the tensors; ordered after everything
@@ -271,7 +281,7 @@ fcdp_status fcdp_host_cache_free(void *host);
  * *store_cache = 0).  backward_source: always the host cache; FCDP_ESTATE if
  * the class is still dirty (no forward has stored it).  optimizer_step marks
  * the trainable class of every layer dirty (frozen stays clean for ever).
- * host_mode must be FCDP_SRC_HOST_DMA or FCDP_SRC_HOST_ZEROCOPY.
+ * host_mode must be one of the three FCDP_SRC_HOST_* sources.
  */
 fcdp_status fcdp_cache_state_create(int32_t n_layers, fcdp_cache_state **out);
 void fcdp_cache_state_destroy(fcdp_cache_state *state);
@@ -317,11 +327,23 @@ fcdp_status fcdp_link_bytes(int32_t reset, int64_t *stored, int64_t *fetched);
 const char *fcdp_status_string(fcdp_status status);
 const char *fcdp_last_error(void);
 
-/* Launch-shape knobs for measurement sweeps (block size, bytes per work item,
- * workgroups per compute unit, non-temporal access).  Unknown name or a value
- * outside the documented range -> FCDP_EINVAL.  Knobs that shape the copy
- * tables take effect for layouts built afterwards.  Not needed for normal
- * use; the defaults are the measured best on MI355X. */
+/* Launch-shape knobs for measurement sweeps.  Unknown name or a value outside
+ * its range -> FCDP_EINVAL.  Not needed for normal use; the defaults are the
+ * measured best on MI355X.  Process-wide, not synchronised with data calls.
+ *   copy_chunk_bytes      piece size of the copy plans, multiple of 4096 in
+ *                         4096..16 MiB (4096); applies to layouts built later
+ *   copy_block            threads per workgroup of the copy kernels, power of
+ *                         two in 64..1024 (128)
+ *   copy_unroll           16-byte vectors in flight per lane: 1, 2, 4, 8 (1)
+ *   copy_nt               non-temporal hint, bit 0 loads, bit 1 stores (3)
+ *   copy_wg_per_cu        cap on workgroups per compute unit, 0 = none (0)
+ *   reduce_block          threads per workgroup of the reduce, 64..256 (64)
+ *   link_max_wgs          workgroups of the zero-copy fetch / store kernels,
+ *                         0 = no bound (64)
+ *   link_block            their threads per workgroup (256)
+ *   link_chunk_bytes      bytes per workgroup trip of the store kernel (16384)
+ *   max_copies_in_flight  host-link DMA copies queued before a call blocks
+ *                         on the oldest, 0 = no bound (2) */
 fcdp_status fcdp_tuning_set(const char *name, int64_t value);
 int64_t fcdp_tuning_get(const char *name); /* -1 if unknown */
 

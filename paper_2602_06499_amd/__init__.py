@@ -6,7 +6,7 @@ does, and raises if it has not been built (there is no CPU fallback).
 """
 from .binding import (  # noqa: F401
     BF16, F32, SRC_DEVICE_SHARDS, SRC_HOST_DMA, SRC_HOST_ZEROCOPY, MAX_G,
-    SRC_DEVICE_RESIDENT, fcdp_cache_store, fcdp_link_bytes,
+    SRC_DEVICE_RESIDENT, SRC_HOST_SCATTER_DMA, fcdp_cache_store, fcdp_link_bytes,
     STORE_NONE, STORE_DMA, STORE_ZEROCOPY,
     FcdpError, Layout, CacheState, HostCache,
     fcdp_layout_build, fcdp_materialize_layer, fcdp_flatten_to_shards,

@@ -18,6 +18,7 @@ SRC_DEVICE_SHARDS = 0
 SRC_HOST_DMA = 1
 SRC_HOST_ZEROCOPY = 2
 SRC_DEVICE_RESIDENT = 3
+SRC_HOST_SCATTER_DMA = 4
 STORE_NONE = 0
 STORE_DMA = 1
 STORE_ZEROCOPY = 2

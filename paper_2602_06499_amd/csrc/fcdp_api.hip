@@ -389,7 +389,7 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
     const char *fn = "fcdp_materialize_layer";
     if (!L) return fail(FCDP_EINVAL, std::string(fn) + ": layout is NULL");
     if (src != FCDP_SRC_DEVICE_SHARDS && src != FCDP_SRC_HOST_DMA && src != FCDP_SRC_HOST_ZEROCOPY &&
-        src != FCDP_SRC_DEVICE_RESIDENT)
+        src != FCDP_SRC_DEVICE_RESIDENT && src != FCDP_SRC_HOST_SCATTER_DMA)
         return fail(FCDP_EINVAL, std::string(fn) + ": unknown source");
     if (store_cache != FCDP_STORE_NONE && store_cache != FCDP_STORE_DMA && store_cache != FCDP_STORE_ZEROCOPY)
         return fail(FCDP_EINVAL, std::string(fn) + ": unknown store_cache mode");
@@ -417,7 +417,7 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
         if (src == FCDP_SRC_HOST_DMA) {
             if (!staging) return fail(FCDP_EINVAL, std::string(fn) + ": FCDP_SRC_HOST_DMA needs a staging buffer");
             if (!aligned16(staging)) return fail(FCDP_EALIGN, std::string(fn) + ": staging is not 16-byte aligned");
-        } else if (flat_bytes) {
+        } else if (src == FCDP_SRC_HOST_ZEROCOPY && flat_bytes) {
             if ((st = mapped_alias(host_cache, fn, &zc_alias)) != FCDP_OK) return st;
         }
     }
@@ -464,6 +464,20 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
         use->staging = staging;
         ctx->fetched_bytes += static_cast<int64_t>(flat_bytes);
         return FCDP_OK;
+    }
+    if (src == FCDP_SRC_HOST_SCATTER_DMA) {
+        // the tensors may still be read by earlier work on `compute`
+        if ((st = order_after(ctx, compute, copy)) != FCDP_OK) return st;
+        const char *h = static_cast<const char *>(host_cache);
+        for (int32_t t = 0; t < L->T; ++t) {
+            if (L->numel[t] == 0) continue;
+            if ((st = copy_admit(ctx)) != FCDP_OK) return st;
+            FCDP_HIP(hipMemcpyAsync(tensor_ptrs[t], h + L->off[t] * L->esz, static_cast<size_t>(L->numel[t]) * L->esz,
+                                    hipMemcpyHostToDevice, copy), "hipMemcpyAsync(H2D, per tensor)");
+            if ((st = copy_enqueued(ctx, copy)) != FCDP_OK) return st;
+        }
+        ctx->fetched_bytes += static_cast<int64_t>(L->N) * L->esz;
+        return order_after(ctx, copy, compute);
     }
     // zero-copy: the kernel's loads cross the host link
     if ((st = order_after(ctx, copy, compute)) != FCDP_OK) return st;
@@ -733,7 +747,10 @@ fcdp_status fcdp_cache_state_create(int32_t n_layers, fcdp_cache_state **out)
 
 void fcdp_cache_state_destroy(fcdp_cache_state *s) { delete s; }
 
-static bool host_mode_ok(fcdp_source m) { return m == FCDP_SRC_HOST_DMA || m == FCDP_SRC_HOST_ZEROCOPY; }
+static bool host_mode_ok(fcdp_source m)
+{
+    return m == FCDP_SRC_HOST_DMA || m == FCDP_SRC_HOST_ZEROCOPY || m == FCDP_SRC_HOST_SCATTER_DMA;
+}
 
 fcdp_status fcdp_cache_state_forward_source(fcdp_cache_state *s, int32_t layer, int32_t klass,
                                             fcdp_source host_mode, fcdp_source *src, int32_t *store_cache)

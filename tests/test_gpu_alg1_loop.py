@@ -22,7 +22,7 @@ def _bits(t):
     return t.cpu().numpy().view(np.uint16)
 
 
-@pytest.mark.parametrize("host_mode", [fcdp.SRC_HOST_DMA, fcdp.SRC_HOST_ZEROCOPY])
+@pytest.mark.parametrize("host_mode", [fcdp.SRC_HOST_DMA, fcdp.SRC_HOST_ZEROCOPY, fcdp.SRC_HOST_SCATTER_DMA])
 @pytest.mark.parametrize("peft", [False, True])
 def test_training_loop_cache_coherence(peft, host_mode):
     nl, G, iters = 3, 4, 4

@@ -44,7 +44,7 @@ def test_full_layer_materialize_and_reduce(name, layer):
         assert np.array_equal(_bits(tensors[t][:k]), want[t]), (name, "device", t)
     assert np.array_equal(H.numpy(np.uint16, Np), oracle.cache_store(shards))
     want2 = oracle.materialize_from_flat(H.numpy(np.uint16, Np), sizes)
-    for mode in (fcdp.SRC_HOST_DMA, fcdp.SRC_HOST_ZEROCOPY):
+    for mode in (fcdp.SRC_HOST_DMA, fcdp.SRC_HOST_ZEROCOPY, fcdp.SRC_HOST_SCATTER_DMA):
         for t in tensors:
             t.zero_()
         torch.cuda.synchronize()

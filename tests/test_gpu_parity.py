@@ -98,7 +98,7 @@ def test_host_cache_store_and_fetch(name, sizes, G, esz):
     torch.cuda.synchronize()
     assert np.array_equal(H.numpy(dt, Np), oracle.cache_store(shards))
     assert np.array_equal(H.numpy(dt, Np), flat)
-    for mode in (fcdp.SRC_HOST_DMA, fcdp.SRC_HOST_ZEROCOPY):
+    for mode in (fcdp.SRC_HOST_DMA, fcdp.SRC_HOST_ZEROCOPY, fcdp.SRC_HOST_SCATTER_DMA):
         out = Arena([k * esz for k in sizes])
         staging = Arena([Np * esz]) if mode == fcdp.SRC_HOST_DMA else None
         torch.cuda.synchronize()
