@@ -282,6 +282,17 @@ def main():
             fcdp.fcdp_pack_trainable(play4, pflatg, ppk, compute)
         fcdp.fcdp_reduce_grad_shard(pg_ptrs, pcfg.G, 0, pS, fcdp.F32, fcdp.F32, pshard, compute)
 
+    # whole-model layout: the LoRA parameters of all layers packed in one launch
+    wl = pcfg.layers
+    wlay = fcdp.fcdp_layout_build(list(pcfg.numel) * wl, list(pcfg.trainable) * wl, pcfg.G, 2)
+    wlay.prepare()
+    wflat = torch.zeros(wlay.padded_numel, dtype=torch.bfloat16, device=dev).normal_(0, 0.02)
+    wpacked = torch.zeros(wlay.packed_numel, dtype=torch.bfloat16, device=dev)
+    torch.cuda.synchronize()
+    wpack_us = 1e3 * time_kernel(lambda: fcdp.fcdp_pack_trainable(wlay, wflat, wpacked, compute), reps=30)
+    wunpack_us = 1e3 * time_kernel(lambda: fcdp.fcdp_unpack_trainable(wlay, wpacked, wflat, compute), reps=30)
+    w_bytes = wlay.trainable_numel * 2
+    del wflat
     unfused_us = 1e3 * time_kernel(unfused, reps=30)
     fused_us = 1e3 * time_kernel(lambda: fcdp.fcdp_reduce_trainable_shard(
         play4, fg_ptrs, 0, fcdp.F32, fcdp.F32, pshard, compute), reps=50)
@@ -342,6 +353,10 @@ def main():
                       "forward_store_d2h": round(d2h_gbps, 2), "backward_fetch_h2d": round(h2d_gbps, 2),
                       "frac_d2h": round(d2h_gbps / LINK_PEAK_GBPS, 4), "frac_h2d": round(h2d_gbps / LINK_PEAK_GBPS, 4),
                       "probe_h2d": round(link["h2d"], 2), "probe_d2h": round(link["d2h"], 2),
+                      # backward sweep per layer against the longer of its two parts
+                      "backward_overlap_efficiency": round(
+                          max(layer_bytes / (link["h2d"] * 1e9) * 1e3, k1_ms + k3_ms) / (bwd_ms / L), 4)
+                      if link_fetched else None,
                       "one_layer_dma_fetch_plus_unflatten_ms": round(dma_ms, 3),
                       "one_layer_zero_copy_ms": round(zc_ms, 3),
                       "one_layer_scatter_dma_ms": round(sc_ms, 3),
@@ -354,7 +369,10 @@ def main():
                  "unpack_us": round(unpack_us, 2), "reduce_packed_us": round(pred_us, 2),
                  "grad_shard_from_flat_grads_us": {"G_packs_then_reduce": round(unfused_us, 2),
                                                    "fused_reduce_trainable_shard": round(fused_us, 2)},
-                 "trainable_bytes": play.trainable_numel * 2},
+                 "trainable_bytes": play.trainable_numel * 2,
+                 "whole_model_%d_layers" % wl: {"trainable_bytes": w_bytes, "pack_us": round(wpack_us, 2),
+                                                "unpack_us": round(wunpack_us, 2),
+                                                "pack_gbps": round(2 * w_bytes / (wpack_us * 1e-6) / 1e9, 1)}},
         "cpu_baseline": cpu,
     }
     cache.free()

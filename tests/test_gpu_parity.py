@@ -481,3 +481,37 @@ def test_reduce_trainable_shard_parity(name, sizes, tr, G, in_dt, out_dt):
         _cmp_reduce(got, want, out_dt)
         out.check_guards()
     arena.check_guards()
+
+
+def test_whole_model_layout_many_tensors():
+    """One layout over every layer's tensors (more tensors than one launch's
+    pointer window): unflatten runs as several launches, pack and unpack as
+    one; all against the oracle."""
+    layer = [4096, 96, 96, 2048, 64, 64, 7000, 33]
+    tr_layer = [0, 1, 1, 0, 1, 1, 0, 0]
+    nl, G = 40, 4                               # 320 tensors
+    sizes, tr = layer * nl, tr_layer * nl
+    tensors = _rand_tensors(31, sizes, np.uint16)
+    flat = oracle.flatten(tensors, G)
+    shards = oracle.split(flat, G)
+    L = fcdp.fcdp_layout_build(sizes, tr, G, 2)
+    sh = Arena([L.shard_numel * 2] * G)
+    for r in range(G):
+        sh.fill(r, shards[r])
+    out = Arena([k * 2 for k in sizes])
+    fcdp.fcdp_materialize_layer(L, fcdp.SRC_DEVICE_SHARDS, sh.ptrs(), None, None, out.ptrs())
+    torch.cuda.synchronize()
+    for t in range(len(sizes)):
+        assert np.array_equal(out.get(t, np.uint16), tensors[t]), t
+    out.check_guards()
+    fa = Arena([flat.size * 2]); fa.fill(0, flat)
+    pa = Arena([L.packed_numel * 2])
+    fcdp.fcdp_pack_trainable(L, fa.ptr(0), pa.ptr(0), None)
+    torch.cuda.synchronize()
+    assert np.array_equal(pa.get(0, np.uint16), oracle.pack(flat, sizes, tr, G))
+    pa.check_guards()
+    back = Arena([L.shard_numel * 2] * G)
+    fcdp.fcdp_flatten_to_shards(L, out.ptrs(), back.ptrs(), None)
+    torch.cuda.synchronize()
+    for r in range(G):
+        assert np.array_equal(back.get(r, np.uint16), shards[r])
