@@ -33,7 +33,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 LINK_PEAK_GBPS = 63.0           # PCIe Gen5 x16 per direction, 128b/130b
 
 # HBM bytes per unflatten launch measured with rocprofv3 --pmc (FETCH_SIZE
-# x 1.99978, WRITE_SIZE x 1.0, the factors the same counters show for the
+# x 1.99984, WRITE_SIZE x 1.0, the factors the same counters show for the
 # plain copy of known size); profiles/unflatten_reduce_llama7b_g8_hbm_traffic.md
 MEASURED_TRAFFIC = {"llama7b_g8": 822.2e6}
 MEASURED_TRAFFIC_REDUCE = {"llama7b_g8": 910.7e6}
