@@ -191,11 +191,13 @@ def bf16_rne(x: np.ndarray) -> np.ndarray:
 
 
 def reduce(partials: Sequence[np.ndarray], elem_offset: int, count: int,
-           out_dtype: int) -> np.ndarray:
+           out_dtype: int, scale=None) -> np.ndarray:
     """Rank-order fp32 sum of G partial gradient slices.
 
     partials: G arrays, float32 (fp32 input) or uint16 (bf16 input).
     out_dtype: BF16 -> uint16 result, F32 -> float32 result.
+    scale: None for the plain sum; a float multiplies the finished sum once
+    in fp32 (1/G gives the mean).
     """
     dt = partials[0].dtype
     if dt == np.float32:
@@ -209,10 +211,18 @@ def reduce(partials: Sequence[np.ndarray], elem_offset: int, count: int,
             raise ValueError("partial too small or dtype mismatch")
     out = np.empty(count, dtype=np.float32 if out_dtype == F32 else np.uint16)
     ps = [_c(p) for p in partials]
-    _check(lib().fcdp_oracle_reduce(
-        _ptr_array(ps), ctypes.c_int32(len(ps)), ctypes.c_int64(elem_offset),
-        ctypes.c_int64(count), ctypes.c_int32(in_dtype),
-        ctypes.c_int32(out_dtype), _p(out)), "reduce")
+    if scale is None:
+        _check(lib().fcdp_oracle_reduce(
+            _ptr_array(ps), ctypes.c_int32(len(ps)),
+            ctypes.c_int64(elem_offset), ctypes.c_int64(count),
+            ctypes.c_int32(in_dtype), ctypes.c_int32(out_dtype), _p(out)),
+            "reduce")
+    else:
+        _check(lib().fcdp_oracle_reduce_scaled(
+            _ptr_array(ps), ctypes.c_int32(len(ps)),
+            ctypes.c_int64(elem_offset), ctypes.c_int64(count),
+            ctypes.c_int32(in_dtype), ctypes.c_int32(out_dtype),
+            ctypes.c_float(scale), _p(out)), "reduce_scaled")
     return out
 
 
@@ -253,7 +263,7 @@ def unpack(packed: np.ndarray, flat: np.ndarray, numel: Sequence[int],
 
 def reduce_trainable(flat_partials: Sequence[np.ndarray], numel: Sequence[int],
                      trainable: Sequence[int], G: int, rank: int,
-                     out_dtype: int, q: int = 64) -> np.ndarray:
+                     out_dtype: int, q: int = 64, scale=None) -> np.ndarray:
     """This rank's shard of the summed trainable gradients.
 
     The composition of two definitions above: every rank's flat gradient is
@@ -262,4 +272,4 @@ def reduce_trainable(flat_partials: Sequence[np.ndarray], numel: Sequence[int],
     """
     packed = [pack(p, numel, trainable, G, q) for p in flat_partials]
     Sp = packed[0].size // G
-    return reduce(packed, rank * Sp, Sp, out_dtype)
+    return reduce(packed, rank * Sp, Sp, out_dtype, scale)

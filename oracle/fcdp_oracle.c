@@ -281,6 +281,42 @@ int fcdp_oracle_reduce(const void *const *partials, int32_t G, int64_t e0,
     return ORACLE_OK;
 }
 
+/*
+ * The same reduction followed by one multiplication (the mean over ranks when
+ * scale = 1/G; Alg. 1 names the collective, not whether it sums or averages,
+ * so both are offered):
+ *   acc as above, then acc = acc * scale, one more binary32 rounding,
+ *   out[k] = acc (fp32)  or  bf16_rne(acc).
+ * The scale multiplies the finished sum, never the terms.
+ */
+int fcdp_oracle_reduce_scaled(const void *const *partials, int32_t G,
+                              int64_t e0, int64_t count, int32_t in_dtype,
+                              int32_t out_dtype, float scale, void *out)
+{
+    if (G < 1 || count < 0) return ORACLE_EINVAL;
+    for (int64_t k = 0; k < count; ++k) {
+        float acc;
+        if (in_dtype == 1)
+            acc = ((const float *)partials[0])[e0 + k];
+        else
+            acc = bf16_to_f32(((const uint16_t *)partials[0])[e0 + k]);
+        for (int32_t g = 1; g < G; ++g) {
+            float v;
+            if (in_dtype == 1)
+                v = ((const float *)partials[g])[e0 + k];
+            else
+                v = bf16_to_f32(((const uint16_t *)partials[g])[e0 + k]);
+            acc = acc + v;
+        }
+        acc = acc * scale;
+        if (out_dtype == 1)
+            ((float *)out)[k] = acc;
+        else
+            ((uint16_t *)out)[k] = fcdp_oracle_bf16_rne(acc);
+    }
+    return ORACLE_OK;
+}
+
 /* ------------------------------------------------------------- pack/unpack */
 
 /*

@@ -12,6 +12,8 @@ import test_oracle_pins as pins
 
 SRC = os.path.join(os.path.dirname(oracle.__file__), "fcdp_oracle.c")
 
+SCALED = "int fcdp_oracle_reduce_scaled("
+
 MUTATIONS = {
     "reduce_starts_from_plus_zero": ("            acc = ((const float *)partials[0])[e0 + k];",
                                      "            acc = 0.0f + ((const float *)partials[0])[e0 + k];"),
@@ -42,6 +44,17 @@ MUTATIONS = {
                           "    (void)Np;"),
     "unpack_writes_frozen_too": ("        if (trainable[t]) {\n            for (int64_t j = 0; j < n[t]; ++j)\n                put_elem(f, off_t + j, p, c + j, esz);\n            c += n[t];\n        }",
                                  "        if (trainable[t] || t == 0) {\n            for (int64_t j = 0; j < n[t]; ++j)\n                put_elem(f, off_t + j, p, c + j, esz);\n            c += n[t];\n        }"),
+    # edits of the scaled reduction: (old, new, text after which to look)
+    "scaled_forgets_scale": ("        acc = acc * scale;\n", "", SCALED),
+    "scaled_divides_by_reciprocal": ("        acc = acc * scale;", "        acc = acc / (1.0f / scale);", SCALED),
+    "scaled_scales_the_terms": [
+        ("            acc = ((const float *)partials[0])[e0 + k];",
+         "            acc = ((const float *)partials[0])[e0 + k] * scale;", SCALED),
+        ("            acc = acc + v;", "            acc = acc + v * scale;", SCALED),
+        ("        acc = acc * scale;\n", "", SCALED)],
+    "scaled_rounds_to_bf16_before_scaling": (
+        "        acc = acc * scale;",
+        "        if (out_dtype == 0) acc = bf16_to_f32(fcdp_oracle_bf16_rne(acc));\n        acc = acc * scale;", SCALED),
     "split_uses_wrong_stride": ("            put_elem(s, k, f, (int64_t)r * S + k, esz);", "            put_elem(s, k, f, (int64_t)r * S + (k + (r > 0)) % S, esz);"),
 }
 
@@ -56,6 +69,8 @@ CHECKS = [
     (pins.test_reduce_order_and_start_value, [()]),
     (pins.test_reduce_bf16_inputs, [()]),
     (pins.test_reduce_shards_concatenate_to_full_sum, [()]),
+    (pins.test_scaled_reduce_special_cases, [()]),
+    (pins.test_scaled_reduce_hand_worked_cases, [()]),
     (pins.test_bf16_rne_hand_worked_cases, [()]),
     (pins.test_bf16_rne_vs_torch_all_boundaries, [()]),
     (pins.test_pack_unpack_invariants, [(3,), (8,)]),
@@ -79,11 +94,18 @@ def test_pins_pass_on_the_real_oracle():
 
 @pytest.mark.parametrize("name", sorted(MUTATIONS))
 def test_planted_mistake_is_caught(name, tmp_path):
-    old, new = MUTATIONS[name]
+    edits = MUTATIONS[name]
+    if not isinstance(edits, list):
+        edits = [edits]
     text = open(SRC).read()
-    assert text.count(old) >= 1, "mutation site not found: the oracle changed, update this test"
+    for edit in edits:
+        old, new = edit[0], edit[1]
+        start = text.index(edit[2]) if len(edit) > 2 else 0
+        assert text.count(old, start) >= 1, \
+            "mutation site not found: the oracle changed, update this test"
+        text = text[:start] + text[start:].replace(old, new, 1)
     src = tmp_path / "mutant.c"
-    src.write_text(text.replace(old, new, 1))
+    src.write_text(text)
     so = tmp_path / "mutant.so"
     subprocess.check_call(["gcc", *[f for f in oracle.CFLAGS if f not in ("-Wall", "-Wextra")], "-w",
                            "-o", str(so), str(src)])

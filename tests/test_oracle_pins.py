@@ -355,6 +355,74 @@ def test_reduce_shards_concatenate_to_full_sum():
     assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
 
 
+def test_scaled_reduce_special_cases():
+    """Pins of the scaled reduction (sum, then one multiplication)."""
+    cfg = synth.CONFIGS["gpt2_small_g4"]
+    G, n = 4, 3001
+    parts = [synth.grad_partial_f32(cfg, 1, g, n) for g in range(G)]
+    plain = oracle.reduce(parts, 0, n, oracle.F32)
+    # scale 1 changes nothing, bit for bit, in both output types
+    assert np.array_equal(oracle.reduce(parts, 0, n, oracle.F32, 1.0).view(np.uint32),
+                          plain.view(np.uint32))
+    assert np.array_equal(oracle.reduce(parts, 0, n, oracle.BF16, 1.0),
+                          oracle.reduce(parts, 0, n, oracle.BF16))
+    # a power of two only moves the exponent (no underflow at this magnitude):
+    # the result is ldexp of the plain sum, exactly
+    for e in (-2, -3, 5):
+        got = oracle.reduce(parts, 0, n, oracle.F32, 2.0 ** e)
+        assert np.array_equal(got.view(np.uint32), np.ldexp(plain, e).view(np.uint32))
+    # the mean of two copies of x is x itself (x + x is exact); with values
+    # of 8 significant bits every partial sum k*x, k <= 8, is exact too
+    x = parts[0]
+    got = oracle.reduce([x] * 2, 0, n, oracle.F32, 0.5)
+    assert np.array_equal(got.view(np.uint32), x.view(np.uint32))
+    xb = _bf16_to_f32(synth.to_bf16_bits(x))
+    got = oracle.reduce([xb] * 8, 0, n, oracle.F32, 1.0 / 8)
+    assert np.array_equal(got.view(np.uint32), xb.view(np.uint32))
+    # -1 flips the sign bit only
+    got = oracle.reduce(parts, 0, n, oracle.F32, -1.0)
+    assert np.array_equal(got.view(np.uint32), plain.view(np.uint32) ^ np.uint32(0x80000000))
+    # G = 1: the library's float32 product
+    s = np.float32(1.0) / np.float32(3.0)
+    got = oracle.reduce([x], 0, n, oracle.F32, float(s))
+    assert np.array_equal(got.view(np.uint32), (x * s).view(np.uint32))
+    # against float64: one rounding more than the plain sum
+    st = np.stack(parts).astype(np.float64)
+    got = oracle.reduce(parts, 0, n, oracle.F32, float(s)).astype(np.float64)
+    bound = G * 2.0 ** -24 * np.sum(np.abs(st), axis=0) * float(s) * 1.0001
+    assert np.all(np.abs(got - st.sum(axis=0) * float(s)) <= bound + 1e-45)
+
+
+def test_scaled_reduce_hand_worked_cases():
+    """The scale multiplies the finished sum, not the terms, and it is a
+    multiplication by the given float, not a division by G."""
+    one = np.array([1.0], dtype=np.float32)
+    tiny = np.array([2.0 ** -24], dtype=np.float32)
+    # 1 + 2^-24 is a tie and rounds to 1; times 3 gives 3.  Scaling the terms
+    # first would give fl(3 + 3*2^-24) = 3 + 2^-22.
+    assert oracle.reduce([one, tiny], 0, 1, oracle.F32, 3.0)[0] == np.float32(3.0)
+    # (1 + 2 + 3) * fl(1/3): fl(1/3) = 0x3EAAAAAB = 1/3 + 2^-26/3... the exact
+    # product 6 * 0.3333333432674408 = 2.0000000596 lies within half an ulp
+    # (2^-23) of 2, so the result is 2
+    third = np.array([1.0], dtype=np.float32) / np.float32(3.0)
+    assert third.view(np.uint32)[0] == 0x3EAAAAAB
+    parts = [np.array([v], dtype=np.float32) for v in (1.0, 2.0, 3.0)]
+    assert oracle.reduce(parts, 0, 1, oracle.F32, float(third[0]))[0] == np.float32(2.0)
+    # 5 * fl(1/3) = 1.66666671633..., which rounds to 0x3FD55556, while the
+    # division 5/3 rounds to 0x3FD55555
+    five = [np.array([5.0], dtype=np.float32)]
+    assert oracle.reduce(five, 0, 1, oracle.F32, float(third[0])).view(np.uint32)[0] == 0x3FD55556
+    assert (np.float32(5.0) / np.float32(3.0)).view(np.uint32) == 0x3FD55555
+    # bf16 output rounds once, after the multiplication: (1 + 2^-8) * 1 would
+    # be a bf16 tie -> 1.0 (0x3F80); times (1 + 2^-10) it lies above the tie
+    a = np.array([1.0 + 2.0 ** -8], dtype=np.float32)
+    assert oracle.reduce([a], 0, 1, oracle.BF16)[0] == 0x3F80
+    assert oracle.reduce([a], 0, 1, oracle.BF16, 1.0 + 2.0 ** -10)[0] == 0x3F81
+    # zeros keep the sign rule of a product: +0 * -1 = -0
+    z = np.array([0.0], dtype=np.float32)
+    assert oracle.reduce([z, z], 0, 1, oracle.F32, -1.0).view(np.uint32)[0] == 0x80000000
+
+
 # ----------------------------------------------------------------- bf16 cast
 
 def test_bf16_rne_hand_worked_cases():
