@@ -242,6 +242,31 @@ fcdp_status fcdp_reduce_trainable_shard(const fcdp_layout *layout,
                                         fcdp_dtype out, void *out_shard,
                                         fcdp_stream stream);
 
+/* The two sums above followed by one multiplication.  Alg. 1 names the
+ * collective ("ReduceScatter(grad W_t)") without saying whether ranks are
+ * summed or averaged; scale = 1/G gives the mean, and a loss-scale's inverse
+ * can ride along.  For every output element
+ *     acc = the rank-order sum as defined above
+ *     out[k] = acc * scale               one more binary32 rounding
+ *     (then the bf16 rounding when out == FCDP_BF16)
+ * The scale multiplies the finished sum, never the terms, and it is a
+ * multiplication by the given float (not a division by G).  scale = 1 gives
+ * the unscaled entry points' results bit for bit; zero-tail positions of the
+ * trainable variant give (+0) * scale.  A scale that is not finite is
+ * FCDP_EINVAL; all other arguments and errors are those of the unscaled
+ * entry points. */
+fcdp_status fcdp_reduce_grad_shard_scaled(const void *const *partial_ptrs,
+                                          int32_t G, int64_t elem_offset,
+                                          int64_t count, fcdp_dtype in,
+                                          fcdp_dtype out, float scale,
+                                          void *out_shard, fcdp_stream stream);
+fcdp_status fcdp_reduce_trainable_shard_scaled(const fcdp_layout *layout,
+                                               const void *const *flat_grad_ptrs,
+                                               int32_t rank, fcdp_dtype in,
+                                               fcdp_dtype out, float scale,
+                                               void *out_shard,
+                                               fcdp_stream stream);
+
 /* --------------------------------------------------- PEFT pack and unpack
  * Under PEFT only trainable parameters cross the node boundary (Sec. 4.5,
  * Alg. 1's dirty branch and its reduce-scatter of grad W_t).

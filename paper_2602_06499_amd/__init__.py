@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     FcdpError, Layout, CacheState, HostCache,
     fcdp_layout_build, fcdp_materialize_layer, fcdp_flatten_to_shards,
     fcdp_reduce_grad_shard, fcdp_reduce_trainable_shard, fcdp_pack_trainable, fcdp_unpack_trainable,
+    fcdp_reduce_grad_shard_scaled, fcdp_reduce_trainable_shard_scaled,
     fcdp_host_cache_alloc, fcdp_host_cache_free, fcdp_tuning_set,
     fcdp_tuning_get, fcdp_probe_copy, fcdp_last_error, load_library,
     library_path, pointer_array, fcdp_timing_enable, fcdp_timing_collect,

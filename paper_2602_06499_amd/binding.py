@@ -42,6 +42,7 @@ EXPORTS = [
     "fcdp_layout_prepare",
     "fcdp_materialize_layer", "fcdp_cache_store", "fcdp_flatten_to_shards",
     "fcdp_reduce_grad_shard", "fcdp_reduce_trainable_shard",
+    "fcdp_reduce_grad_shard_scaled", "fcdp_reduce_trainable_shard_scaled",
     "fcdp_pack_trainable", "fcdp_unpack_trainable",
     "fcdp_host_cache_alloc", "fcdp_host_cache_free",
     "fcdp_cache_state_create", "fcdp_cache_state_destroy",
@@ -106,6 +107,8 @@ def load_library() -> ctypes.CDLL:
     lib.fcdp_link_bytes.argtypes = [i32, c.POINTER(i64), c.POINTER(i64)]
     lib.fcdp_reduce_grad_shard.argtypes = [vp, i32, i64, i64, c.c_int, c.c_int, vp, vp]
     lib.fcdp_reduce_trainable_shard.argtypes = [vp, vp, i32, c.c_int, c.c_int, vp, vp]
+    lib.fcdp_reduce_grad_shard_scaled.argtypes = [vp, i32, i64, i64, c.c_int, c.c_int, c.c_float, vp, vp]
+    lib.fcdp_reduce_trainable_shard_scaled.argtypes = [vp, vp, i32, c.c_int, c.c_int, c.c_float, vp, vp]
     lib.fcdp_pack_trainable.argtypes = [vp, vp, vp, vp]
     lib.fcdp_unpack_trainable.argtypes = [vp, vp, vp, vp]
     lib.fcdp_host_cache_alloc.argtypes = [c.c_size_t, c.c_int, c.POINTER(vp), c.POINTER(vp)]
@@ -282,6 +285,23 @@ def fcdp_reduce_trainable_shard(layout: Layout, flat_grad_ptrs, rank: int,
     _check(load_library().fcdp_reduce_trainable_shard(
         layout.handle, _ptr_array(flat_grad_ptrs), rank, in_dtype, out_dtype,
         _ptr(out_shard), _stream(stream)))
+
+
+def fcdp_reduce_grad_shard_scaled(partial_ptrs, G: int, elem_offset: int,
+                                  count: int, in_dtype: int, out_dtype: int,
+                                  scale: float, out_shard, stream=None) -> None:
+    _check(load_library().fcdp_reduce_grad_shard_scaled(
+        _ptr_array(partial_ptrs), G, elem_offset, count, in_dtype, out_dtype,
+        scale, _ptr(out_shard), _stream(stream)))
+
+
+def fcdp_reduce_trainable_shard_scaled(layout: Layout, flat_grad_ptrs, rank: int,
+                                       in_dtype: int, out_dtype: int,
+                                       scale: float, out_shard,
+                                       stream=None) -> None:
+    _check(load_library().fcdp_reduce_trainable_shard_scaled(
+        layout.handle, _ptr_array(flat_grad_ptrs), rank, in_dtype, out_dtype,
+        scale, _ptr(out_shard), _stream(stream)))
 
 
 def fcdp_pack_trainable(layout: Layout, flat, packed, stream=None) -> None:

@@ -6,6 +6,7 @@
 #include <unistd.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -543,7 +544,15 @@ fcdp_status fcdp_reduce_grad_shard(const void *const *partial_ptrs, int32_t G, i
                                    int64_t count, fcdp_dtype in, fcdp_dtype out, void *out_shard,
                                    fcdp_stream stream)
 {
+    return fcdp_reduce_grad_shard_scaled(partial_ptrs, G, elem_offset, count, in, out, 1.0f, out_shard, stream);
+}
+
+fcdp_status fcdp_reduce_grad_shard_scaled(const void *const *partial_ptrs, int32_t G, int64_t elem_offset,
+                                          int64_t count, fcdp_dtype in, fcdp_dtype out, float scale,
+                                          void *out_shard, fcdp_stream stream)
+{
     const char *fn = "fcdp_reduce_grad_shard";
+    if (!std::isfinite(scale)) return fail(FCDP_EINVAL, std::string(fn) + ": scale is not finite");
     if (!partial_ptrs) return fail(FCDP_EINVAL, std::string(fn) + ": partial_ptrs is NULL");
     if (G < 1) return fail(FCDP_EINVAL, std::string(fn) + ": G must be >= 1");
     if (G > FCDP_MAX_G) return fail(FCDP_ESIZE, std::string(fn) + ": G exceeds FCDP_MAX_G (64)");
@@ -564,7 +573,7 @@ fcdp_status fcdp_reduce_grad_shard(const void *const *partial_ptrs, int32_t G, i
         if (overlap && !(pb == ob && ie == oe))
             return fail(FCDP_EINVAL, std::string(fn) + ": out_shard overlaps an input other than exactly in place");
     }
-    hipError_t e = static_cast<hipError_t>(fcdp::launch_reduce(partial_ptrs, G, elem_offset, count, in, out, out_shard, stream,
+    hipError_t e = static_cast<hipError_t>(fcdp::launch_reduce(partial_ptrs, G, elem_offset, count, in, out, scale, out_shard, stream,
                                                                count > 0 ? timing_events(FCDP_KERNEL_REDUCE) : fcdp::LaunchEvents()));
     if (e != hipSuccess) return hip_fail(e, "launch reduce");
     return FCDP_OK;
@@ -574,7 +583,15 @@ fcdp_status fcdp_reduce_trainable_shard(const fcdp_layout *L, const void *const 
                                         int32_t rank, fcdp_dtype in, fcdp_dtype out, void *out_shard,
                                         fcdp_stream stream)
 {
+    return fcdp_reduce_trainable_shard_scaled(L, flat_grad_ptrs, rank, in, out, 1.0f, out_shard, stream);
+}
+
+fcdp_status fcdp_reduce_trainable_shard_scaled(const fcdp_layout *L, const void *const *flat_grad_ptrs,
+                                               int32_t rank, fcdp_dtype in, fcdp_dtype out, float scale,
+                                               void *out_shard, fcdp_stream stream)
+{
     const char *fn = "fcdp_reduce_trainable_shard";
+    if (!std::isfinite(scale)) return fail(FCDP_EINVAL, std::string(fn) + ": scale is not finite");
     if (!L) return fail(FCDP_EINVAL, std::string(fn) + ": layout is NULL");
     if (!flat_grad_ptrs) return fail(FCDP_EINVAL, std::string(fn) + ": flat_grad_ptrs is NULL");
     if (rank < 0 || rank >= L->G) return fail(FCDP_EINVAL, std::string(fn) + ": rank out of range");
@@ -614,7 +631,7 @@ fcdp_status fcdp_reduce_trainable_shard(const fcdp_layout *L, const void *const 
     if (hi > std::max(lo, L->N_t)) add(-1, std::max(lo, L->N_t) - lo, hi - std::max(lo, L->N_t)); // zero tail
     for (const fcdp::ReduceRuns &b : batches) {
         hipError_t e = static_cast<hipError_t>(fcdp::launch_reduce_runs(
-            flat_grad_ptrs, L->G, b, in, out, out_shard, stream, timing_events(FCDP_KERNEL_REDUCE_TRAINABLE)));
+            flat_grad_ptrs, L->G, b, in, out, scale, out_shard, stream, timing_events(FCDP_KERNEL_REDUCE_TRAINABLE)));
         if (e != hipSuccess) return hip_fail(e, "launch trainable reduce");
     }
     return FCDP_OK;

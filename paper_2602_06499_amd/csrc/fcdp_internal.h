@@ -127,7 +127,7 @@ struct CopyLaunch {
 };
 int launch_copy(const CopyLaunch &c, void *stream);
 int launch_reduce(const void *const *partials, int32_t G, int64_t elem_offset,
-                  int64_t count, int in_dtype, int out_dtype, void *out,
+                  int64_t count, int in_dtype, int out_dtype, float scale, void *out,
                   void *stream, const LaunchEvents &ev = LaunchEvents());
 struct PlainCopy {
     int64_t chunk = 0, block = 0, unroll = 0, max_wgs = 0; // 0 = the copy_* knobs
@@ -145,7 +145,7 @@ struct ReduceRuns {
     int64_t count[kMaxReduceRuns];
 };
 int launch_reduce_runs(const void *const *partials, int32_t G, const ReduceRuns &runs,
-                       int in_dtype, int out_dtype, void *out, void *stream,
+                       int in_dtype, int out_dtype, float scale, void *out, void *stream,
                        const LaunchEvents &ev = LaunchEvents());
 int launch_plain_copy(void *dst, const void *src, size_t bytes, void *stream,
                       const PlainCopy &shape = PlainCopy());

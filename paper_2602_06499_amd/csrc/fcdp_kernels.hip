@@ -224,6 +224,7 @@ struct ReduceArgs {
     char *out;
     int64_t count;
     int32_t G;
+    float scale; // multiplies the finished sum; 1.0f leaves every value as it is
 };
 
 __device__ __forceinline__ uint32_t bf16_rne_bits(float x)
@@ -340,8 +341,11 @@ __device__ __forceinline__ void reduce_tile(const ReduceArgs &a, int64_t b0, int
     if constexpr (REM > 0)
         add_group<REM, IN_F32, ALIGNED, UNROLL, NT>(a, full, lidx, acc);
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u)
+    for (int u = 0; u < UNROLL; ++u) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[u][c] = acc[u][c] * a.scale;
         if (!GUARD || idx[u] < nvec) store4<OUT_F32, kReduceNTStore>(a.out, idx[u], acc[u]);
+    }
 }
 
 // REM = G mod kGroup is a template parameter, so the rank loop is a counted
@@ -374,6 +378,7 @@ __global__ void __launch_bounds__(256) reduce_ranks(const ReduceArgs a)
                         reinterpret_cast<const uint16_t *>(a.p[g])[k]) << 16);
             acc = acc + v;
         }
+        acc = acc * a.scale;
         if constexpr (OUT_F32)
             reinterpret_cast<float *>(a.out)[k] = acc;
         else
@@ -388,7 +393,7 @@ constexpr int kRunPieceElems = 2048; // elements one workgroup reduces
 struct ReduceRunArgs {
     int32_t first_piece[kMaxReduceRuns + 1]; // prefix sums; unused = INT32_MAX
     int32_t G;
-    int32_t reserved;
+    float scale;
     int64_t src_off[kMaxReduceRuns]; // elements; < 0: the run is zeros
     int64_t dst_off[kMaxReduceRuns];
     int64_t count[kMaxReduceRuns];
@@ -449,6 +454,8 @@ __global__ void __launch_bounds__(256) reduce_runs(const ReduceRunArgs a)
 #pragma unroll
                 for (int c = 0; c < 4; ++c) acc[c] = 0.0f;
             }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[c] = acc[c] * a.scale;
             if (vec_store) {
                 store4<OUT_F32, false>(a.out + d * oes, v, acc);
             } else {
@@ -464,7 +471,7 @@ __global__ void __launch_bounds__(256) reduce_runs(const ReduceRunArgs a)
             } else {
                 acc = 0.0f;
             }
-            store_elem<OUT_F32>(a.out, d + k, acc);
+            store_elem<OUT_F32>(a.out, d + k, acc * a.scale);
         }
     }
 }
@@ -591,7 +598,7 @@ int launch_copy(const CopyLaunch &c, void *stream)
 }
 
 int launch_reduce_runs(const void *const *partials, int32_t G, const ReduceRuns &runs,
-                       int in_dtype, int out_dtype, void *out, void *stream,
+                       int in_dtype, int out_dtype, float scale, void *out, void *stream,
                        const LaunchEvents &ev)
 {
     if (runs.n_runs <= 0) return hipSuccess;
@@ -613,7 +620,7 @@ int launch_reduce_runs(const void *const *partials, int32_t G, const ReduceRuns 
     if (total >= 0x7fffffff) return hipErrorInvalidValue;
     args.first_piece[kMaxReduceRuns] = static_cast<int32_t>(total);
     args.G = G;
-    args.reserved = 0;
+    args.scale = scale;
     for (int g = 0; g < FCDP_MAX_G; ++g)
         args.p[g] = g < G ? static_cast<const char *>(partials[g]) : nullptr;
     args.out = static_cast<char *>(out);
@@ -655,7 +662,7 @@ int launch_plain_copy(void *dst, const void *src, size_t bytes, void *stream,
 }
 
 int launch_reduce(const void *const *partials, int32_t G, int64_t elem_offset,
-                  int64_t count, int in_dtype, int out_dtype, void *out,
+                  int64_t count, int in_dtype, int out_dtype, float scale, void *out,
                   void *stream, const LaunchEvents &ev)
 {
     if (count <= 0) return hipSuccess;
@@ -673,6 +680,7 @@ int launch_reduce(const void *const *partials, int32_t G, int64_t elem_offset,
     args.out = static_cast<char *>(out);
     args.count = count;
     args.G = G;
+    args.scale = scale;
     const Tuning &t = tuning();
     const int64_t block = t.reduce_block;
     const int64_t nvec = count >> 2;

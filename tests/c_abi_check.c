@@ -39,6 +39,7 @@ int main(void)
     CHECK(fcdp_layout_build(numel, trainable, 4, 0, 2, 64, &L) == FCDP_EINVAL);
     CHECK(strstr(fcdp_last_error(), "G must be") != NULL);
     CHECK(fcdp_reduce_grad_shard(NULL, 2, 0, 8, FCDP_F32, FCDP_F32, NULL, NULL) == FCDP_EINVAL);
+    CHECK(fcdp_reduce_grad_shard_scaled(NULL, 2, 0, 8, FCDP_F32, FCDP_F32, 0.5f, NULL, NULL) == FCDP_EINVAL);
     CHECK(strcmp(fcdp_status_string(FCDP_OK), "FCDP_OK") == 0);
 
     CHECK(fcdp_cache_state_create(2, &st) == FCDP_OK);

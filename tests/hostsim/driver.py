@@ -91,7 +91,7 @@ def check_layer(name, sizes, G, esz, offset):
     L.destroy()
 
 
-def check_reduce(G, count, e0, in_dt, out_dt, offset):
+def check_reduce(G, count, e0, in_dt, out_dt, offset, scale=None):
     g = synth.rng(0, G * 1000 + count % 997, synth.KIND_GRAD, 9)
     n = e0 + count
     parts = []
@@ -99,11 +99,15 @@ def check_reduce(G, count, e0, in_dt, out_dt, offset):
         x = (g.standard_normal(n, dtype=np.float32)
              * np.exp2(g.integers(-20, 20, size=n)).astype(np.float32))
         parts.append(synth.to_bf16_bits(x) if in_dt == oracle.BF16 else x)
-    want = oracle.reduce(parts, e0, count, out_dt)
+    want = oracle.reduce(parts, e0, count, out_dt, scale)
     d_parts = [dev(p, offset) for p in parts]
     osz = 4 if out_dt == oracle.F32 else 2
     d_out = Buf(count * osz, offset)
-    fcdp.fcdp_reduce_grad_shard(d_parts, G, e0, count, in_dt, out_dt, d_out, None)
+    if scale is None:
+        fcdp.fcdp_reduce_grad_shard(d_parts, G, e0, count, in_dt, out_dt, d_out, None)
+    else:
+        fcdp.fcdp_reduce_grad_shard_scaled(d_parts, G, e0, count, in_dt, out_dt, scale,
+                                           d_out, None)
     got = d_out.view(np.uint32 if osz == 4 else np.uint16)
     assert np.array_equal(got, want.view(got.dtype)), ("reduce", G, count, e0, in_dt, out_dt)
 
@@ -139,13 +143,18 @@ def check_peft(name, sizes, tr, G, esz):
             x = synth.rng(0, r, synth.KIND_GRAD, 5).standard_normal(n, dtype=np.float32)
             parts.append(synth.to_bf16_bits(x) if in_dt == oracle.BF16 else x)
         for rank in sorted({0, G // 2, G - 1}):
-            want = oracle.reduce_trainable(parts, sizes, tr, G, rank, out_dt)
             d_parts = [dev(p) for p in parts]
             osz = 4 if out_dt == oracle.F32 else 2
-            d_out = Buf(want.size * osz)
-            fcdp.fcdp_reduce_trainable_shard(L, d_parts, rank, in_dt, out_dt, d_out, None)
-            got = d_out.view(np.uint32 if osz == 4 else np.uint16)
-            assert np.array_equal(got, want.view(got.dtype)), (name, "reduce_trainable", rank)
+            for scale in (None, float(np.float32(-1.0 / G))):
+                want = oracle.reduce_trainable(parts, sizes, tr, G, rank, out_dt, scale=scale)
+                d_out = Buf(want.size * osz)
+                if scale is None:
+                    fcdp.fcdp_reduce_trainable_shard(L, d_parts, rank, in_dt, out_dt, d_out, None)
+                else:
+                    fcdp.fcdp_reduce_trainable_shard_scaled(L, d_parts, rank, in_dt, out_dt,
+                                                            scale, d_out, None)
+                got = d_out.view(np.uint32 if osz == 4 else np.uint16)
+                assert np.array_equal(got, want.view(got.dtype)), (name, "reduce_trainable", rank, scale)
 
 
 def planted_short_output():
@@ -193,7 +202,8 @@ def main():
                               (oracle.BF16, oracle.BF16), (oracle.BF16, oracle.F32)):
             print("reduce", G, count, e0, in_dt, out_dt, flush=True)
             check_reduce(G, count, e0, in_dt, out_dt, 0)
-            n += 1
+            check_reduce(G, count, e0, in_dt, out_dt, 0, float(np.float32(1.0 / G)))
+            n += 2
     peft_cases = [
         ("lora_like", [4096, 64, 64, 4096, 128, 128, 9000], [0, 1, 1, 0, 1, 1, 0], 4, 2),
         ("none_trainable", [100, 200], [0, 0], 2, 2),

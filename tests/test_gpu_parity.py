@@ -483,6 +483,102 @@ def test_reduce_trainable_shard_parity(name, sizes, tr, G, in_dt, out_dt):
     arena.check_guards()
 
 
+SCALED_CASES = [
+    # G, count, e0, in, out, scale
+    (8, 300007, 0, oracle.F32, oracle.F32, 1.0 / 8),
+    (8, 300007, 0, oracle.F32, oracle.BF16, 1.0 / 8),
+    (3, 70001, 5, oracle.F32, oracle.F32, 1.0 / 3),
+    (7, 33333, 3, oracle.F32, oracle.BF16, 1.0 / 7),
+    (17, 40000, 7, oracle.F32, oracle.F32, 1.0 / 17),
+    (5, 50001, 0, oracle.BF16, oracle.BF16, 0.2),
+    (32, 9999, 5, oracle.BF16, oracle.F32, 1.0 / (32 * 1024.0)),
+    (4, 4099, 1, oracle.F32, oracle.F32, -3.5),
+    (2, 1003, 0, oracle.F32, oracle.F32, 0.0),
+    (6, 3, 0, oracle.F32, oracle.F32, 1.0 / 6),
+]
+
+
+@pytest.mark.parametrize("G,count,e0,in_dt,out_dt,scale", SCALED_CASES)
+def test_scaled_reduce_parity(G, count, e0, in_dt, out_dt, scale):
+    """Sum in rank order, then one multiplication by the given float."""
+    scale = float(np.float32(scale))
+    g = synth.rng(0, 1700 + G, synth.KIND_GRAD, count % 1000)
+    total = e0 + count + 5
+    parts = []
+    for r in range(G):
+        x = g.standard_normal(total, dtype=np.float32) * np.float32(10.0 ** int(g.integers(-5, 2)))
+        parts.append(x if in_dt == oracle.F32 else synth.to_bf16_bits(x))
+    want = oracle.reduce(parts, e0, count, out_dt, scale)
+    ies = 4 if in_dt == oracle.F32 else 2
+    oes = 4 if out_dt == oracle.F32 else 2
+    arena = Arena([total * ies] * G)
+    for r in range(G):
+        arena.fill(r, parts[r])
+    out = Arena([count * oes])
+    fcdp.fcdp_reduce_grad_shard_scaled(arena.ptrs(), G, e0, count, in_dt, out_dt,
+                                       scale, out.ptr(0), None)
+    torch.cuda.synchronize()
+    got = out.get(0, np.float32 if out_dt == oracle.F32 else np.uint16)
+    _cmp_reduce(got, want, out_dt)
+    out.check_guards()
+
+
+def test_scale_one_is_the_plain_sum_and_denormals_survive():
+    """scale = 1 gives the unscaled entry point's bits, including denormal
+    and negative-zero results; scaling into the denormal range rounds as IEEE
+    arithmetic does, with no flush."""
+    n = 4096 + 3
+    g = synth.rng(0, 1801, synth.KIND_GRAD)
+    parts = [g.standard_normal(n, dtype=np.float32) for _ in range(3)]
+    for p in parts:
+        p[:64] = np.arange(1, 65, dtype=np.uint32).view(np.float32)   # denormals
+        p[64:80] = -0.0
+    arena = Arena([n * 4] * 3)
+    for r in range(3):
+        arena.fill(r, parts[r])
+    a, b, c = Arena([n * 4]), Arena([n * 4]), Arena([n * 4])
+    fcdp.fcdp_reduce_grad_shard(arena.ptrs(), 3, 0, n, fcdp.F32, fcdp.F32, a.ptr(0), None)
+    fcdp.fcdp_reduce_grad_shard_scaled(arena.ptrs(), 3, 0, n, fcdp.F32, fcdp.F32, 1.0, b.ptr(0), None)
+    tiny = float(np.float32(2.0 ** -130))
+    fcdp.fcdp_reduce_grad_shard_scaled(arena.ptrs(), 3, 0, n, fcdp.F32, fcdp.F32, tiny, c.ptr(0), None)
+    torch.cuda.synchronize()
+    plain = a.get(0, np.uint32)
+    assert np.array_equal(plain, b.get(0, np.uint32))
+    assert np.array_equal(plain, oracle.reduce(parts, 0, n, oracle.F32).view(np.uint32))
+    want = oracle.reduce(parts, 0, n, oracle.F32, tiny)
+    assert np.count_nonzero((want != 0) & (np.abs(want) < 2.0 ** -126)) > 100    # denormal results
+    assert np.array_equal(c.get(0, np.uint32), want.view(np.uint32))
+
+
+@pytest.mark.parametrize("name,sizes,tr,G,in_dt,out_dt", TRAINABLE_REDUCE_CASES[:4],
+                         ids=[c[0] for c in TRAINABLE_REDUCE_CASES[:4]])
+def test_scaled_reduce_trainable_shard_parity(name, sizes, tr, G, in_dt, out_dt):
+    """The fused pack + reduce with the mean's scale, every rank."""
+    L = fcdp.fcdp_layout_build(sizes, tr, G, 2)
+    Np = L.padded_numel
+    scale = float(np.float32(-1.0) / np.float32(G))      # a negative scale: the zero tail is -0
+    g = synth.rng(0, 1900 + G, synth.KIND_GRAD, len(sizes))
+    parts = []
+    for r in range(G):
+        x = g.standard_normal(Np, dtype=np.float32)
+        parts.append(x if in_dt == oracle.F32 else synth.to_bf16_bits(x))
+    ies = 4 if in_dt == oracle.F32 else 2
+    oes = 4 if out_dt == oracle.F32 else 2
+    arena = Arena([Np * ies] * G)
+    for r in range(G):
+        arena.fill(r, parts[r])
+    Sp = L.packed_numel // G
+    for rank in range(G):
+        want = oracle.reduce_trainable(parts, sizes, tr, G, rank, out_dt, scale=scale)
+        out = Arena([Sp * oes])
+        fcdp.fcdp_reduce_trainable_shard_scaled(L, arena.ptrs(), rank, in_dt, out_dt,
+                                                scale, out.ptr(0), None)
+        torch.cuda.synchronize()
+        got = out.get(0, np.float32 if out_dt == oracle.F32 else np.uint16)
+        _cmp_reduce(got, want, out_dt)
+        out.check_guards()
+
+
 def test_whole_model_layout_many_tensors():
     """One layout over every layer's tensors (more tensors than one launch's
     pointer window): unflatten runs as several launches, pack and unpack as

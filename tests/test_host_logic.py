@@ -190,6 +190,12 @@ def test_data_call_argument_errors_before_any_enqueue():
     # partial overlap of output and an input; exact in-place with a narrower output dtype
     assert err(r, [0x1000, 0x8000], 2, 0, 100, fcdp.F32, fcdp.F32, 0x1010) == "FCDP_EINVAL"
     assert err(r, [0x1000, 0x8000], 2, 0, 100, fcdp.F32, fcdp.BF16, 0x1000) == "FCDP_EINVAL"
+    rs = fcdp.fcdp_reduce_grad_shard_scaled
+    assert err(rs, [0x100, 0x200], 2, 0, 10, fcdp.F32, fcdp.F32, float("nan"), 0x9000) == "FCDP_EINVAL"
+    assert err(rs, [0x100, 0x200], 2, 0, 10, fcdp.F32, fcdp.F32, float("inf"), 0x9000) == "FCDP_EINVAL"
+    assert err(rs, [0x100, 0x204], 2, 0, 10, fcdp.F32, fcdp.F32, 0.5, 0x9000) == "FCDP_EALIGN"
+    assert err(fcdp.fcdp_reduce_trainable_shard_scaled, L, [0x100000, 0x200000, 0x300000, 0x400000],
+               0, fcdp.F32, fcdp.F32, float("-inf"), 0x9000) == "FCDP_EINVAL"
     p = fcdp.fcdp_pack_trainable
     assert err(p, L, None, 0x100) == "FCDP_EINVAL"
     assert err(p, L, 0x104, 0x10000) == "FCDP_EALIGN"
