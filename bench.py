@@ -55,8 +55,13 @@ def parse():
     ap.add_argument("--timed-dispatches", type=int, default=-1,
                     help="how many kernel dispatches carry timing events (-1 = all of the timed steps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-small-leg", action="store_true",
+                    help="skip the launch-bound GPT-2-small leg (eager against a HIP graph)")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--cpu-sample-layers", type=int, default=16)
+    ap.add_argument("--cpu-threads", type=int, default=8,
+                    help="threads of the all-threads oracle leg (one layer each, ~1.3 GB of host memory per thread)")
+    ap.add_argument("--probe-gib", type=int, default=2, help="size of the host-link probe copy")
     return ap.parse_args()
 
 
@@ -217,7 +222,7 @@ def main():
             assert torch.equal(hc, gathered[L - 1].cpu().view(torch.int16)), "host cache mismatch"
 
     # ---- host-link probe: one large pinned copy each way ----------------
-    probe_bytes = 2 << 30
+    probe_bytes = args.probe_gib << 30
     pin = torch.empty(probe_bytes, dtype=torch.uint8, pin_memory=True)
     dbuf = torch.empty(probe_bytes, dtype=torch.uint8, device=dev)
     link = {}
@@ -297,8 +302,55 @@ def main():
     fused_us = 1e3 * time_kernel(lambda: fcdp.fcdp_reduce_trainable_shard(
         play4, fg_ptrs, 0, fcdp.F32, fcdp.F32, pshard, compute), reps=50)
 
+    # ---- launch-bound leg: GPT-2-small layers, eager against a HIP graph --
+    small = None
+    if not args.no_small_leg:
+        scfg = synth.CONFIGS["gpt2_small_g4"]
+        slay = fcdp.fcdp_layout_build(scfg.numel, None, scfg.G, 2)
+        slay.prepare()
+        sL, sS, sN = 12, slay.shard_numel, slay.numel     # GPT-2-small has 12 such layers
+        sflat = [torch.zeros(slay.padded_numel, dtype=torch.bfloat16, device=dev).normal_(0, 0.02)
+                 for _ in range(sL)]
+        ssh = [fcdp.pointer_array([f.data_ptr() + r * sS * 2 for r in range(scfg.G)]) for f in sflat]
+        sten = [torch.empty((k + 7) // 8 * 8, dtype=torch.bfloat16, device=dev) for k in scfg.numel]
+        sten_p = fcdp.pointer_array(sten)
+        sgr = torch.zeros(scfg.G, sS, dtype=torch.float32, device=dev).normal_(0, 1e-3)
+        sgr_p = fcdp.pointer_array([sgr.data_ptr() + r * sS * 4 for r in range(scfg.G)])
+        sout = torch.empty(sS, dtype=torch.float32, device=dev)
+
+        def sweep():        # backward-like sweep from resident shards: K1 + K3 per layer
+            for l in range(sL - 1, -1, -1):
+                fcdp.fcdp_materialize_layer(slay, fcdp.SRC_DEVICE_SHARDS, ssh[l], None, None,
+                                            sten_p, False, compute, None)
+                fcdp.fcdp_reduce_grad_shard(sgr_p, scfg.G, 0, sS, fcdp.F32, fcdp.F32, sout, compute)
+
+        torch.cuda.synchronize()
+        fcdp.fcdp_timing_enable(4 * sL + 8)
+        sweep(); sweep()
+        torch.cuda.synchronize()
+        n1, t1 = fcdp.fcdp_timing_collect(fcdp.KERNEL_UNFLATTEN)
+        n3, t3 = fcdp.fcdp_timing_collect(fcdp.KERNEL_REDUCE)
+        fcdp.fcdp_timing_enable(0)
+        eager_ms = time_kernel(sweep, reps=20)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=compute, capture_error_mode="thread_local"):
+            sweep()
+        with torch.cuda.stream(compute):
+            graph_ms = time_kernel(graph.replay, reps=20)
+        if not args.no_check:
+            off = slay.offsets
+            for t, k in enumerate(scfg.numel):
+                assert torch.equal(sten[t][:k], sflat[0][off[t]:off[t] + k]), "graph replay mismatch"
+        small = {"workload": "%s: %d layers of %.1f MB, unflatten + fp32 reduce of %d partials per layer"
+                             % (scfg.name, sL, sN * 2 / 1e6, scfg.G),
+                 "unflatten_kernel_us": round(1e3 * t1 / max(n1, 1), 2),
+                 "reduce_kernel_us": round(1e3 * t3 / max(n3, 1), 2),
+                 "eager_us_per_layer": round(1e3 * eager_ms / sL, 2),
+                 "graph_us_per_layer": round(1e3 * graph_ms / sL, 2)}
+        del graph, sflat, sten, sgr, sout
+
     # ---- CPU oracle on a bounded sample of the same workload -------------
-    cpu = None
+    cpu = cpu_par = None
     if not args.no_cpu_baseline:
         import oracle
         oracle.lib()
@@ -318,6 +370,31 @@ def main():
                 assert np.array_equal(tens[0], kept_tensors.get(0, tensors)[0][:cfg.numel[0]].cpu().view(torch.int16).numpy().view(np.uint16))
                 assert np.array_equal(red.view(np.uint32), grad_shard.cpu().numpy().view(np.uint32))
             del tens, tens2, H, red
+        # the same oracle, one layer per thread (ctypes releases the GIL): what the
+        # host's cores give together, still nothing tuned
+        from concurrent.futures import ThreadPoolExecutor
+        n_t = max(1, min(args.cpu_threads, L, os.cpu_count() or 1))
+        work = []
+        for l in range(n_t):
+            flat = gathered[l].cpu().view(torch.int16).numpy().view(np.uint16)
+            work.append(([flat[r * S:(r + 1) * S] for r in range(G)],
+                         [partials[l][r].cpu().numpy() for r in range(G)]))
+
+        def one_layer(w):
+            shards, parts = w
+            H = oracle.cache_store(shards)
+            return (len(oracle.materialize_from_shards(shards, cfg.numel)),
+                    len(oracle.materialize_from_flat(H, cfg.numel)),
+                    oracle.reduce(parts, 0, S, oracle.F32).size)
+
+        with ThreadPoolExecutor(n_t) as pool:
+            t0 = time.perf_counter()
+            list(pool.map(one_layer, work))
+            t_par = time.perf_counter() - t0
+        del work
+        cpu_par = {"value": round(2 * n_t * layer_bytes / t_par / 1e9, 3), "unit": "GB/s",
+                   "cores": n_t, "kind": "oracle, one layer per thread",
+                   "sample": "%d layers at once, %.1f s wall" % (n_t, t_par)}
         cpu = {"value": round(2 * n_s * layer_bytes / t_cpu / 1e9, 3), "unit": "GB/s",
                "cores": 1, "kind": "oracle",
                "sample": "%d of %d layers of %s (materialize from shards, cache store, "
@@ -373,7 +450,9 @@ def main():
                  "whole_model_%d_layers" % wl: {"trainable_bytes": w_bytes, "pack_us": round(wpack_us, 2),
                                                 "unpack_us": round(wunpack_us, 2),
                                                 "pack_gbps": round(2 * w_bytes / (wpack_us * 1e-6) / 1e9, 1)}},
+        "small_layers": small,
         "cpu_baseline": cpu,
+        "cpu_baseline_all_threads": cpu_par,
     }
     cache.free()
     print(json.dumps(out), flush=True)

@@ -32,6 +32,12 @@
  *     that), and a call that would put more than max_copies_in_flight (a
  *     tuning knob, default 2) host-link DMA copies in flight first waits on
  *     the host for the oldest of them.
+ *   - Stream capture: the calls that only launch kernels may be recorded into
+ *     a HIP graph: fcdp_materialize_layer with FCDP_SRC_DEVICE_SHARDS and no
+ *     store, fcdp_flatten_to_shards, the reduce entry points, pack and
+ *     unpack; call fcdp_layout_prepare first and keep timing disabled.  The
+ *     host-cache sources and the store use events and host-side waits and
+ *     must stay outside a capture.
  *   - Every data base pointer must be 16-byte aligned (FCDP_EALIGN if not).
  *     Offsets inside a buffer may be any element index.
  *   - Errors: a status code is returned, nothing is thrown and nothing
