@@ -258,6 +258,11 @@ def main():
     k3b_ms = time_kernel(lambda: fcdp.fcdp_reduce_grad_shard(
         part_ptrs[0], G, 0, S, fcdp.F32, fcdp.BF16, bshard, compute))
 
+    # bf16 partials (half the read bytes): the first half of each fp32 partial viewed as bf16
+    bpart = fcdp.pointer_array([partials[0][r] for r in range(G)])
+    k3bb_ms = time_kernel(lambda: fcdp.fcdp_reduce_grad_shard(
+        bpart, G, 0, S, fcdp.BF16, fcdp.BF16, bshard, compute))
+
     # ---- PEFT leg: LoRA r16 on q,v of the same stack ---------------------
     pcfg = synth.CONFIGS["llama7b_lora_g8"]
     play = fcdp.fcdp_layout_build(pcfg.numel, pcfg.trainable, pcfg.G, 2)
@@ -425,7 +430,8 @@ def main():
                             "traffic": MEASURED_TRAFFIC_REDUCE.get(cfg.name),
                             "bytes_per_launch": k3_bytes, "avg_launch_ms": round(k3_ms, 4),
                             "launches_timed": k3_launches,
-                            "bf16_out_gbps": round((G * S * 4 + S * 2) / (k3b_ms * 1e-3) / 1e9, 1)},
+                            "bf16_out_gbps": round((G * S * 4 + S * 2) / (k3b_ms * 1e-3) / 1e9, 1),
+                            "bf16_in_bf16_out_gbps": round((G * S * 2 + S * 2) / (k3bb_ms * 1e-3) / 1e9, 1)},
         "host_link": {"peak": LINK_PEAK_GBPS, "unit": "GB/s",
                       "forward_store_d2h": round(d2h_gbps, 2), "backward_fetch_h2d": round(h2d_gbps, 2),
                       "frac_d2h": round(d2h_gbps / LINK_PEAK_GBPS, 4), "frac_h2d": round(h2d_gbps / LINK_PEAK_GBPS, 4),

@@ -9,6 +9,7 @@ import re
 
 import numpy as np
 import pytest
+from hypothesis import given, settings, strategies as st
 
 import oracle
 from oracle import alg1
@@ -108,6 +109,45 @@ def test_copy_plans_reproduce_oracle(sizes, G, esz, chunk):
     got = [base.copy().view(np.uint8)]
     _run_plan(L.copy_plan(3), packed, got)
     assert np.array_equal(got[0].view(dt), want)
+
+
+def _covered_exactly_once(plan, dst_sizes):
+    """Every destination byte is written by exactly one row of the plan."""
+    cover = [np.zeros(n, dtype=np.uint8) for n in dst_sizes]
+    for _si, _so, di, do, nb in plan:
+        cover[di][do:do + nb] += 1
+    return all(bool(np.all(c == 1)) for c in cover)
+
+
+@settings(max_examples=60, deadline=None, derandomize=True)
+@given(sizes=st.lists(st.one_of(st.integers(0, 3), st.integers(0, 40000),
+                                st.sampled_from([2048, 4096, 8192, 32768, 2047, 4097])),
+                      min_size=1, max_size=12),
+       G=st.sampled_from([1, 2, 3, 4, 5, 7, 8, 16, 32, 64]),
+       esz=st.sampled_from([2, 4]), chunk=st.sampled_from([4096, 8192, 65536]))
+def test_copy_plans_property(sizes, G, esz, chunk):
+    """Random layouts: the plans are in bounds, write every destination byte
+    exactly once and reproduce the oracle (same checks as above)."""
+    test_copy_plans_reproduce_oracle(sizes, G, esz, chunk)
+    tr = [(t * 5 + G) % 2 == 0 for t in range(len(sizes))]
+    old = fcdp.fcdp_tuning_get("copy_chunk_bytes")
+    fcdp.fcdp_tuning_set("copy_chunk_bytes", chunk)
+    try:
+        L = fcdp.fcdp_layout_build(sizes, tr, G, esz)
+    finally:
+        fcdp.fcdp_tuning_set("copy_chunk_bytes", old)
+    assert _covered_exactly_once(L.copy_plan(0), [k * esz for k in sizes])
+    assert _covered_exactly_once(L.copy_plan(1), [L.shard_numel * esz] * G)
+    assert _covered_exactly_once(L.copy_plan(2), [L.packed_numel * esz])
+    # unpack writes exactly the trainable ranges of the flat buffer
+    cover = np.zeros(L.padded_numel * esz, dtype=np.uint8)
+    for _si, _so, _di, do, nb in L.copy_plan(3):
+        cover[do:do + nb] += 1
+    want = np.zeros_like(cover)
+    for t, k in enumerate(sizes):
+        if tr[t]:
+            want[L.offsets[t] * esz:(L.offsets[t] + k) * esz] = 1
+    assert np.array_equal(cover, want)
 
 
 def test_copy_plan_at_benchmark_shapes():
