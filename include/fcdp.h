@@ -374,7 +374,17 @@ const char *fcdp_last_error(void);
  *   link_block            their threads per workgroup (256)
  *   link_chunk_bytes      bytes per workgroup trip of the store kernel (16384)
  *   max_copies_in_flight  host-link DMA copies queued before a call blocks
- *                         on the oldest, 0 = no bound (2) */
+ *                         on the oldest, 0 = no bound (2)
+ *   debug_poison          0 or 1 (0; the environment variable
+ *                         FCDP_DEBUG_POISON=1 turns it on at load).  A debugging
+ *                         aid: fcdp_materialize_layer first fills every tensor
+ *                         of the layer with the 16-bit pattern 0x7FC1 (a bf16
+ *                         NaN) on `compute`, the staging buffer on `copy` ahead
+ *                         of the fetch, and a store first fills a mapped host
+ *                         cache on `copy`; a consumer that misses one of the
+ *                         documented waits then reads NaNs instead of stale
+ *                         bytes that may happen to be right.  Results are
+ *                         unchanged; each call costs one more pass. */
 fcdp_status fcdp_tuning_set(const char *name, int64_t value);
 int64_t fcdp_tuning_get(const char *name); /* -1 if unknown */
 

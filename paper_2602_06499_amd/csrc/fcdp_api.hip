@@ -305,6 +305,30 @@ fcdp_status mapped_alias(void *host, const char *fn, void **alias)
     return FCDP_OK;
 }
 
+// The device alias of mapped pinned host memory, or NULL; leaves no error.
+void *alias_or_null(void *host)
+{
+    hipPointerAttribute_t attr;
+    std::memset(&attr, 0, sizeof attr);
+    if (hipPointerGetAttributes(&attr, host) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    return attr.type == hipMemoryTypeHost ? attr.devicePointer : nullptr;
+}
+
+// debug_poison: fill every tensor of the layer on `st`
+fcdp_status poison_tensors(const fcdp_layout *L, void *const *tensor_ptrs, hipStream_t st)
+{
+    for (int32_t t = 0; t < L->T; ++t) {
+        if (L->numel[t] == 0) continue;
+        hipError_t e = static_cast<hipError_t>(fcdp::launch_fill(
+            tensor_ptrs[t], static_cast<size_t>(L->numel[t]) * L->esz, fcdp::kPoison, st));
+        if (e != hipSuccess) return hip_fail(e, "launch poison fill");
+    }
+    return FCDP_OK;
+}
+
 // H <- concat(shards): after the producers of the shards (everything on
 // `compute` so far), on the `copy` stream.
 fcdp_status enqueue_store(const fcdp_layout *L, DeviceCtx *ctx, const void *const *shard_ptrs,
@@ -318,6 +342,13 @@ fcdp_status enqueue_store(const fcdp_layout *L, DeviceCtx *ctx, const void *cons
     // H <- concat(shards): after the producers of the shards, beside the scatter
     if ((st = order_after(ctx, compute, copy)) != FCDP_OK) return st;
     char *h = static_cast<char *>(host_cache);
+    if (tune.debug_poison) {
+        // through the mapping, in copy-stream order like the store itself
+        if (void *pa = store_alias ? store_alias : alias_or_null(host_cache)) {
+            hipError_t e = static_cast<hipError_t>(fcdp::launch_fill(pa, flat_bytes, fcdp::kPoison, copy, tune.link_max_wgs));
+            if (e != hipSuccess) return hip_fail(e, "launch poison fill (host cache)");
+        }
+    }
     // contiguous shards (one gather buffer) go out as a single copy
     bool contiguous = true;
     for (int32_t r = 1; r < L->G; ++r)
@@ -436,6 +467,8 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
     if ((st = tables_for_current_device(L, &tabs)) != FCDP_OK) return st;
     const fcdp::Tuning &tune = fcdp::tuning();
 
+    if (tune.debug_poison && (st = poison_tensors(L, tensor_ptrs, compute)) != FCDP_OK) return st;
+
     const void *small[FCDP_MAX_G];
     if (src == FCDP_SRC_DEVICE_SHARDS) {
         if (store_cache && flat_bytes) {
@@ -452,6 +485,10 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
         if ((st = staging_slot(ctx, staging, &use)) != FCDP_OK) return st;
         if (use->staging == staging)
             FCDP_HIP(hipStreamWaitEvent(copy, use->done, 0), "hipStreamWaitEvent(staging)");
+        if (tune.debug_poison) {
+            hipError_t pe = static_cast<hipError_t>(fcdp::launch_fill(staging, flat_bytes, fcdp::kPoison, copy));
+            if (pe != hipSuccess) return hip_fail(pe, "launch poison fill (staging)");
+        }
         if ((st = copy_admit(ctx)) != FCDP_OK) return st;
         FCDP_HIP(hipMemcpyAsync(staging, host_cache, flat_bytes, hipMemcpyHostToDevice, copy), "hipMemcpyAsync(H2D)");
         if ((st = copy_enqueued(ctx, copy)) != FCDP_OK) return st;
@@ -897,6 +934,9 @@ fcdp_status fcdp_tuning_set(const char *name, int64_t v)
     } else if (n == "reduce_block") {
         if (v < 64 || v > 256 || !pow2(v)) return fail(FCDP_EINVAL, "reduce_block: power of two in 64..256");
         t.reduce_block = v;
+    } else if (n == "debug_poison") {
+        if (v != 0 && v != 1) return fail(FCDP_EINVAL, "debug_poison: 0 or 1");
+        t.debug_poison = v;
     } else {
         return fail(FCDP_EINVAL, "fcdp_tuning_set: unknown knob " + n);
     }
@@ -918,6 +958,7 @@ int64_t fcdp_tuning_get(const char *name)
     if (n == "copy_nt") return t.copy_nt;
     if (n == "max_copies_in_flight") return t.max_copies_in_flight;
     if (n == "reduce_block") return t.reduce_block;
+    if (n == "debug_poison") return t.debug_poison;
     return -1;
 }
 

@@ -95,7 +95,13 @@ struct Tuning {
     // to 20-30 GB/s.  2 is also the depth double buffering needs.  0 = off
     int64_t max_copies_in_flight = 2;
     int64_t reduce_block = 64;
+    // debugging aid, off by default (the environment variable FCDP_DEBUG_POISON=1
+    // turns it on at load): outputs are filled with kPoison before the work that
+    // writes them is enqueued, so a consumer that misses a wait reads poison
+    // instead of stale bytes that happen to be right
+    int64_t debug_poison = 0;
 };
+constexpr uint16_t kPoison = 0x7FC1; // a bf16 NaN; 0x7FC17FC1 is an fp32 NaN
 Tuning &tuning();
 
 // host-side table construction (fcdp_layout.cpp)
@@ -149,6 +155,8 @@ int launch_reduce_runs(const void *const *partials, int32_t G, const ReduceRuns 
                        const LaunchEvents &ev = LaunchEvents());
 int launch_plain_copy(void *dst, const void *src, size_t bytes, void *stream,
                       const PlainCopy &shape = PlainCopy());
+// dst 16-byte aligned, bytes even; max_wgs 0 = up to 16384 workgroups
+int launch_fill(void *dst, size_t bytes, uint16_t pattern, void *stream, int64_t max_wgs = 0);
 int device_cu_count();
 
 } // namespace fcdp

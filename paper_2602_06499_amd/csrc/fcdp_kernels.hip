@@ -217,6 +217,26 @@ __global__ void plain_copy(const PlainArgs a)
     }
 }
 
+// Fills a 16-byte aligned buffer of an even number of bytes with a repeated
+// 16-bit pattern (the debug poison).
+struct FillArgs {
+    char *dst;
+    size_t bytes;
+    uint32_t pattern; // the 16-bit pattern in both halves
+};
+
+__global__ void __launch_bounds__(256) fill_pattern(const FillArgs a)
+{
+    const size_t nvec = a.bytes >> 4;
+    const u32x4 v{a.pattern, a.pattern, a.pattern, a.pattern};
+    const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
+    for (size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < nvec; i += stride)
+        reinterpret_cast<u32x4 *>(a.dst)[i] = v;
+    const size_t t = (nvec << 4) + 2 * static_cast<size_t>(threadIdx.x);
+    if (blockIdx.x == 0 && t < a.bytes)
+        *reinterpret_cast<uint16_t *>(a.dst + t) = static_cast<uint16_t>(a.pattern);
+}
+
 // ------------------------------------------------------------------ reduce
 
 struct ReduceArgs {
@@ -631,6 +651,20 @@ int launch_reduce_runs(const void *const *partials, int32_t G, const ReduceRuns 
     if (inf && !outf) return launch_one(reduce_runs<true, false>, grid, block, st, ev, args);
     if (!inf && outf) return launch_one(reduce_runs<false, true>, grid, block, st, ev, args);
     return launch_one(reduce_runs<false, false>, grid, block, st, ev, args);
+}
+
+int launch_fill(void *dst, size_t bytes, uint16_t pattern, void *stream, int64_t max_wgs)
+{
+    if (bytes == 0) return hipSuccess;
+    FillArgs a;
+    a.dst = static_cast<char *>(dst);
+    a.bytes = bytes;
+    a.pattern = static_cast<uint32_t>(pattern) | (static_cast<uint32_t>(pattern) << 16);
+    int64_t grid = static_cast<int64_t>(((bytes >> 4) + 255) / 256);
+    grid = std::max<int64_t>(1, std::min<int64_t>(grid, max_wgs > 0 ? max_wgs : 16384));
+    hipLaunchKernelGGL(fill_pattern, dim3(static_cast<unsigned>(grid)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), a);
+    return hipGetLastError();
 }
 
 int launch_plain_copy(void *dst, const void *src, size_t bytes, void *stream,

@@ -6,6 +6,7 @@
 // order, zero tail padding up to a multiple of G*q, shard r = flat range
 // [r*S, (r+1)*S).
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <limits>
 #include <new>
@@ -70,7 +71,12 @@ const std::string &last_error_ref() { return g_last_error; }
 
 Tuning &tuning()
 {
-    static Tuning t;
+    static Tuning t = [] {
+        Tuning v;
+        const char *e = std::getenv("FCDP_DEBUG_POISON");
+        if (e && e[0] && e[0] != '0') v.debug_poison = 1;
+        return v;
+    }();
     return t;
 }
 

@@ -193,6 +193,12 @@ def main():
         print("layer", name, flush=True)
         check_layer(name, sizes, G, esz, 0)     # the ABI wants 16-byte aligned bases
         n += 1
+    fcdp.fcdp_tuning_set("debug_poison", 1)     # the poison fills, same results
+    for name, sizes, G, esz in layer_cases[:6]:
+        print("layer (poison)", name, flush=True)
+        check_layer(name, sizes, G, esz, 0)
+        n += 1
+    fcdp.fcdp_tuning_set("debug_poison", 0)
     reduce_cases = [(1, 1000, 0), (2, 4099, 0), (3, 7001, 5), (7, 3333, 3),
                     (8, 30007, 0), (9, 1234, 1), (15, 5000, 2), (16, 6553, 0),
                     (17, 4000, 7), (33, 2049, 0), (64, 3001, 11), (5, 3, 0),

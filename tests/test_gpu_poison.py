@@ -1,0 +1,81 @@
+"""The debug poison: with the knob on, outputs are filled with a NaN pattern
+before the work that writes them is enqueued.  Results must not change, and
+the fill must really happen where the header says."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2602_06499_amd as fcdp
+from paper_2602_06499_amd import synth
+from gpu_util import Arena
+
+import test_gpu_alg1_loop as loop
+import test_gpu_stream_order as order
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture
+def poison():
+    fcdp.fcdp_tuning_set("debug_poison", 1)
+    try:
+        yield
+    finally:
+        fcdp.fcdp_tuning_set("debug_poison", 0)
+
+
+@pytest.mark.parametrize("host_mode", [fcdp.SRC_HOST_DMA, fcdp.SRC_HOST_ZEROCOPY, fcdp.SRC_HOST_SCATTER_DMA])
+def test_training_loop_under_poison(poison, host_mode):
+    loop.test_training_loop_cache_coherence(True, host_mode)
+    loop.test_training_loop_cache_coherence(False, host_mode)
+
+
+def test_adaptive_caching_under_poison(poison):
+    loop.test_adaptive_gpu_caching(0.5)
+
+
+def test_stream_order_under_poison(poison):
+    order.test_scatter_waits_for_a_late_fetch()
+    order.test_host_sources_wait_for_a_late_store(fcdp.SRC_HOST_ZEROCOPY)
+    order.test_store_waits_for_a_late_producer(fcdp.STORE_DMA)
+    order.test_staging_reuse_waits_for_a_late_scatter()
+    order.test_scatter_dma_waits_for_earlier_readers()
+
+
+def test_poison_is_written_first(poison):
+    """The fill is real: with `copy` held back, the scatter of a DMA fetch
+    cannot start, so a snapshot of the tensors taken meanwhile must show the
+    pattern everywhere; afterwards the tensors hold the layer."""
+    sizes, G = [70000, 5, 65536, 9], 4
+    L = fcdp.fcdp_layout_build(sizes, None, G, 2)
+    Np = L.padded_numel
+    tensors = [synth.rng(0, 3, synth.KIND_MISC, t).integers(0, 65536, size=k, dtype=np.uint16)
+               for t, k in enumerate(sizes)]
+    flat = oracle.flatten(tensors, G)
+    H = fcdp.fcdp_host_cache_alloc(Np * 2)
+    H.numpy(np.uint16, Np)[:] = flat
+    out = Arena([k * 2 for k in sizes])
+    staging = Arena([Np * 2])
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    snap = torch.empty_like(out.buf)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(copy):
+        torch.cuda._sleep(order.SPIN)
+    fcdp.fcdp_materialize_layer(L, fcdp.SRC_HOST_DMA, None, H, staging.ptr(0), out.ptrs(),
+                                fcdp.STORE_NONE, compute, copy)
+    time.sleep(0.003)             # the fill runs at once on the idle stream (microseconds)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        snap.copy_(out.buf)       # the scatter is still blocked behind `copy`
+    torch.cuda.synchronize()
+    h = snap.cpu().numpy()
+    for o, nb in out.ranges:
+        assert np.all(h[o:o + nb].view(np.uint16) == 0x7FC1), "tensor was not poisoned ahead of the fetch"
+    for t, k in enumerate(sizes):
+        assert np.array_equal(out.get(t, np.uint16), tensors[t])
+    out.check_guards()
+    staging.check_guards()
+    H.free()
