@@ -611,3 +611,73 @@ def test_whole_model_layout_many_tensors():
     torch.cuda.synchronize()
     for r in range(G):
         assert np.array_equal(back.get(r, np.uint16), shards[r])
+
+
+def test_random_layouts_end_to_end():
+    """Forty seeded random layers (tensor counts 1..40, sizes 0..400k, every G
+    class, both element sizes, random trainable masks) through every byte
+    mover: unflatten + store, the three host fetches, flatten, pack, unpack."""
+    g = synth.rng(0, 4242, synth.KIND_MISC, 5)
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    for case in range(40):
+        T = int(g.integers(1, 41))
+        G = int(g.choice([1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64]))
+        esz = int(g.choice([2, 4]))
+        sizes = synth.random_layer(9000 + case, T=T, max_numel=int(g.choice([300, 5000, 400000])))
+        tr = [int(v) for v in g.integers(0, 2, size=T)]
+        dt = np.uint16 if esz == 2 else np.uint32
+        tensors = _rand_tensors(5000 + case, sizes, dt)
+        flat = oracle.flatten(tensors, G)
+        shards = oracle.split(flat, G)
+        L = fcdp.fcdp_layout_build(sizes, tr, G, esz)
+        S, Np, Pn = L.shard_numel, L.padded_numel, L.packed_numel
+        tag = (case, T, G, esz)
+        sh = Arena([S * esz] * G)
+        for r in range(G):
+            sh.fill(r, shards[r])
+        H = fcdp.fcdp_host_cache_alloc(max(Np * esz, 16))
+        H.numpy(np.uint8)[:] = 0x5A
+        out = Arena([k * esz for k in sizes])
+        torch.cuda.synchronize()
+        fcdp.fcdp_materialize_layer(L, fcdp.SRC_DEVICE_SHARDS, sh.ptrs(), H, None, out.ptrs(),
+                                    fcdp.STORE_DMA if case % 2 else fcdp.STORE_ZEROCOPY, compute, copy)
+        torch.cuda.synchronize()
+        for t in range(T):
+            assert np.array_equal(out.get(t, dt), tensors[t]), tag + ("shards", t)
+        out.check_guards()
+        assert np.array_equal(H.numpy(dt, Np), flat), tag + ("store",)
+        for mode in (fcdp.SRC_HOST_DMA, fcdp.SRC_HOST_ZEROCOPY, fcdp.SRC_HOST_SCATTER_DMA):
+            o2 = Arena([k * esz for k in sizes])
+            stg = Arena([max(Np * esz, 16)])
+            torch.cuda.synchronize()
+            fcdp.fcdp_materialize_layer(L, mode, None, H, stg.ptr(0), o2.ptrs(), fcdp.STORE_NONE,
+                                        compute, copy)
+            torch.cuda.synchronize()
+            for t in range(T):
+                assert np.array_equal(o2.get(t, dt), tensors[t]), tag + (mode, t)
+            o2.check_guards()
+            stg.check_guards()
+        back = Arena([S * esz] * G)
+        fcdp.fcdp_flatten_to_shards(L, out.ptrs(), back.ptrs(), compute)
+        fl = Arena([max(Np * esz, 16)])
+        fl.buf[fl.ranges[0][0]:fl.ranges[0][0] + Np * esz] = torch.from_numpy(flat.view(np.uint8).copy()).cuda()
+        pk = Arena([max(Pn * esz, 16)])
+        torch.cuda.synchronize()
+        fcdp.fcdp_pack_trainable(L, fl.ptr(0), pk.ptr(0), compute)
+        torch.cuda.synchronize()
+        for r in range(G):
+            assert np.array_equal(back.get(r, dt), shards[r]), tag + ("flatten", r)
+        back.check_guards()
+        assert np.array_equal(pk.get(0, dt)[:Pn], oracle.pack(flat, sizes, tr, G)), tag + ("pack",)
+        pk.check_guards()
+        newp = _rand_tensors(7000 + case, [Pn], dt)[0]
+        want = flat.copy()
+        oracle.unpack(newp, want, sizes, tr)
+        if Pn:
+            pk.buf[pk.ranges[0][0]:pk.ranges[0][0] + Pn * esz] = torch.from_numpy(newp.view(np.uint8).copy()).cuda()
+        torch.cuda.synchronize()
+        fcdp.fcdp_unpack_trainable(L, pk.ptr(0), fl.ptr(0), compute)
+        torch.cuda.synchronize()
+        assert np.array_equal(fl.get(0, dt)[:Np], want), tag + ("unpack",)
+        fl.check_guards()
+        H.free()
