@@ -408,7 +408,11 @@ __global__ void __launch_bounds__(256) reduce_ranks(const ReduceArgs a)
 }
 
 // ---- reduce over runs (trainable ranges of unpacked gradients) ------------
-constexpr int kRunPieceElems = 2048; // elements one workgroup reduces
+// A LoRA layer's shard is a few tens of thousands of elements, so the kernel is
+// launch-bound: small pieces spread it over enough workgroups (measured:
+// 256..2048 elements per piece are within noise of each other, 4.2-4.5 us).
+constexpr int kRunPieceElems = 512; // elements one workgroup reduces
+constexpr int kRunBlock = 128;      // one 4-element vector per thread
 
 struct ReduceRunArgs {
     int32_t first_piece[kMaxReduceRuns + 1]; // prefix sums; unused = INT32_MAX
@@ -464,9 +468,22 @@ __global__ void __launch_bounds__(256) reduce_runs(const ReduceRunArgs a)
         for (int64_t v = threadIdx.x; v < nvec; v += blockDim.x) {
             float acc[4] = {-0.0f, -0.0f, -0.0f, -0.0f};
             if (so >= 0) {
-                for (int g = 0; g < a.G; ++g) {
+                const int64_t sb = s * (IN_F32 ? 4 : 2);
+                int g = 0;
+                // four ranks' loads are issued before their adds; the adds
+                // stay in rank order
+                for (; g + 4 <= a.G; g += 4) {
+                    float x[4][4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) load4<IN_F32, false, false>(a.p[g + k] + sb, v, x[k]);
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) acc[c] = acc[c] + x[k][c];
+                }
+                for (; g < a.G; ++g) {
                     float x[4];
-                    load4<IN_F32, false, false>(a.p[g] + s * (IN_F32 ? 4 : 2), v, x);
+                    load4<IN_F32, false, false>(a.p[g] + sb, v, x);
 #pragma unroll
                     for (int c = 0; c < 4; ++c) acc[c] = acc[c] + x[c];
                 }
@@ -644,7 +661,7 @@ int launch_reduce_runs(const void *const *partials, int32_t G, const ReduceRuns 
     for (int g = 0; g < FCDP_MAX_G; ++g)
         args.p[g] = g < G ? static_cast<const char *>(partials[g]) : nullptr;
     args.out = static_cast<char *>(out);
-    const dim3 grid(static_cast<unsigned>(total)), block(256);
+    const dim3 grid(static_cast<unsigned>(total)), block(kRunBlock);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool inf = in_dtype == FCDP_F32, outf = out_dtype == FCDP_F32;
     if (inf && outf) return launch_one(reduce_runs<true, true>, grid, block, st, ev, args);
