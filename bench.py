@@ -412,10 +412,10 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 copies, f32 adds", "data": "synthetic",
-        "config": {"workload": "%s: %d layers, hidden 4096, FFN 11008, G=%d shards/layer, "
+        "config": {"workload": "%s: %d layers of %d tensors, %.1f M parameters each, G=%d shards/layer, "
                                "forward unflatten + D2H cache store (%s), backward host fetch (%s) + "
                                "unflatten + fp32 reduce of %d partials"
-                               % (cfg.name, L, G, args.store, args.fetch, G),
+                               % (cfg.name, L, T, N / 1e6, G, args.store, args.fetch, G),
                    "layer_bytes": layer_bytes, "fetch": args.fetch, "store": args.store},
         "roofline": {"kernel": "copy_pieces<1,3> (unflatten: forward from the gathered shards, "
                                "backward from the DMA staging buffer)", "bound": "hbm",
