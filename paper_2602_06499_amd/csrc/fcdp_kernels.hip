@@ -6,8 +6,12 @@
 //                   HBM (or by the host link when the source is host memory).
 //   reduce_ranks -- rank-order fp32 sum of G partial gradient slices with an
 //                   optional bf16 (nearest-even) store.  Bound by HBM reads.
+//   reduce_runs  -- the same sum over the trainable ranges of G unpacked flat
+//                   gradients, written in packed order (pack and reduce in
+//                   one launch); launch-bound at PEFT sizes.
 //   plain_copy   -- contiguous copy with the same inner loop; the known-size
 //                   reference for counter calibration.
+//   fill_pattern -- 16-bit pattern fill behind the debug poison.
 //
 // Nothing here is a contraction, so no MFMA and no LDS staging: every byte is
 // read once and written once, there is no reuse to stage.  What matters is
