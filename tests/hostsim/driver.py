@@ -210,7 +210,16 @@ def main():
             check_reduce(G, count, e0, in_dt, out_dt, 0)
             check_reduce(G, count, e0, in_dt, out_dt, 0, float(np.float32(1.0 / G)))
             n += 2
-    peft_cases = [
+    for name, sizes, tr, G, esz in PEFT_CASES():
+        print("peft", name, flush=True)
+        check_peft(name, sizes, tr, G, esz)
+        n += 1
+    print("hostsim ok: %d cases" % n, flush=True)
+
+
+def PEFT_CASES():
+    cfg = synth.CONFIGS["gpt2_small_g4"]
+    return [
         ("lora_like", [4096, 64, 64, 4096, 128, 128, 9000], [0, 1, 1, 0, 1, 1, 0], 4, 2),
         ("none_trainable", [100, 200], [0, 0], 2, 2),
         ("all_trainable_odd", [333, 1, 0, 4097], [1, 1, 1, 1], 3, 2),
@@ -218,11 +227,6 @@ def main():
         ("gpt2_bias_only", list(cfg.numel),
          [1 if k < 10000 else 0 for k in cfg.numel], cfg.G, 2),
     ]
-    for name, sizes, tr, G, esz in peft_cases:
-        print("peft", name, flush=True)
-        check_peft(name, sizes, tr, G, esz)
-        n += 1
-    print("hostsim ok: %d cases" % n, flush=True)
 
 
 if __name__ == "__main__":
