@@ -166,6 +166,35 @@ def test_copy_plan_at_benchmark_shapes():
         assert plan[:, 0].min() >= 0 and plan[:, 0].max() < cfg.G
 
 
+def test_huge_layer_plans_stay_bounded():
+    """A 16 GiB layer (beyond any shipped shape): the piece size grows so that
+    no table exceeds about 4 M pieces, offsets stay 64-bit clean, and the plan
+    still covers every byte exactly (checked by sums and by order, without
+    allocating the layer)."""
+    sizes = [2 ** 32, 2 ** 32 + 12345, 7, 2 ** 31 + 1]
+    G = 64
+    L = fcdp.fcdp_layout_build(sizes, [0, 1, 1, 0], G, 2)
+    lay = oracle.layout(sizes, G)
+    assert (L.numel, L.padded_numel, L.shard_numel) == (lay["N"], lay["N_pad"], lay["S"])
+    lib = fcdp.load_library()
+    for which, total in ((0, L.numel * 2), (1, L.padded_numel * 2),
+                         (2, L.packed_numel * 2), (3, L.trainable_numel * 2)):
+        n = lib.fcdp_layout_copy_plan(L.handle, which, None, 0)
+        assert 0 < n <= (1 << 22) + 4 * (len(sizes) + G)
+        rows = np.zeros((n, 5), dtype=np.int64)
+        assert lib.fcdp_layout_copy_plan(L.handle, which, ctypes.c_void_p(rows.ctypes.data), n) == n
+        assert int(rows[:, 4].sum()) == total
+        assert rows[:, 4].min() > 0 and np.all(rows[:, 4] % 2 == 0)
+        assert rows[:, 1].min() >= 0 and rows[:, 3].min() >= 0
+        # destination ranges of one buffer follow each other without gap or overlap
+        for di in np.unique(rows[:, 2])[:3]:
+            r = rows[rows[:, 2] == di]
+            r = r[np.argsort(r[:, 3], kind="stable")]
+            assert np.all(r[1:, 3] == r[:-1, 3] + r[:-1, 4])
+    segs = np.array(L.segments(), dtype=np.int64).reshape(-1, 5)
+    assert np.array_equal(segs, oracle.segments(sizes, G))
+
+
 def test_layout_build_errors():
     E = fcdp.FcdpError
     for args, name in [
