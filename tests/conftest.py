@@ -12,6 +12,15 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def pytest_sessionstart(session):
+    """Tests load the library that is built; only if nothing is built yet do
+    they build it (hipcc cross-compiles for gfx950 without a GPU)."""
+    from paper_2602_06499_amd import binding
+    if not os.path.exists(binding.library_path()):
+        from paper_2602_06499_amd import build
+        build.build()
+
+
 def _have_gpu() -> bool:
     try:
         import torch
