@@ -15,7 +15,7 @@ layers, G = 8 shards per layer, bf16 parameters, fp32 gradient partials):
                           reduce their G packed gradient partials, unpack
 
 Inputs are synthetic and seeded, already resident in HBM / pinned memory when
-the timed region starts.  Prints ONE JSON line (see README).
+the timed region starts.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
