@@ -35,9 +35,9 @@
 
 /*
  * Offset table.  off has T+1 entries.  (Sec. 2.1 / Sec. 6.1: parameters are
- * split evenly over all G GPUs; the flattening order, the tight packing and
- * the zero tail padding to a multiple of G*q are the layout reading stated
- * in the design notes.)
+ * split evenly over all G GPUs.  The paper does not print the layout it
+ * inherits; the reading used here: tensors end to end in the order given,
+ * tightly packed, zero elements at the tail up to a multiple of G*q.)
  */
 int fcdp_oracle_layout(const int64_t *n, int32_t T, int32_t G, int32_t q,
                        int64_t *off, int64_t *N_out, int64_t *N_pad_out,
