@@ -207,14 +207,14 @@ struct PlainArgs {
     const char *src;
     char *dst;
     size_t bytes;
+    size_t n_chunks; // ceil(bytes / chunk), from the host (no 64-bit division in the kernel)
     uint32_t chunk;
 };
 
 template <int UNROLL, int HINT>
 __global__ void plain_copy(const PlainArgs a)
 {
-    const size_t n_chunks = (a.bytes + a.chunk - 1) / a.chunk;
-    for (size_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    for (size_t c = blockIdx.x; c < a.n_chunks; c += gridDim.x) {
         const size_t o = c * a.chunk;
         const uint32_t n = static_cast<uint32_t>(a.bytes - o < a.chunk ? a.bytes - o : a.chunk);
         copy_piece<UNROLL, HINT>(a.src + o, a.dst + o, n, false, threadIdx.x, blockDim.x);
@@ -709,6 +709,7 @@ int launch_plain_copy(void *dst, const void *src, size_t bytes, void *stream,
     pa.src = static_cast<const char *>(src);
     pa.dst = static_cast<char *>(dst);
     pa.bytes = bytes;
+    pa.n_chunks = n_chunks;
     pa.chunk = chunk;
     if (unroll >= 8) return launch_plain_h<8>(pa, g, b, hint, st, shape.ev);
     if (unroll >= 4) return launch_plain_h<4>(pa, g, b, hint, st, shape.ev);
