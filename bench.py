@@ -413,7 +413,8 @@ def main():
         "value": round(value, 3), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 copies, f32 adds", "data": "synthetic",
+        "dtype": "f32", "dtype_note": "the only arithmetic on the path is the fp32 rank-order sum; "
+        "bf16 parameters are moved as bit patterns", "data": "synthetic",
         "config": {"workload": "%s: %d layers of %d tensors, %.1f M parameters each, G=%d shards/layer, "
                                "forward unflatten + D2H cache store (%s), backward host fetch (%s) + "
                                "unflatten + fp32 reduce of %d partials"
