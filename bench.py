@@ -357,7 +357,7 @@ def main():
         del graph, sflat, sten, sgr, sout
 
     # ---- CPU oracle on a bounded sample of the same workload -------------
-    cpu = cpu_par = None
+    cpu = cpu_par = cpu_peft = None
     if not args.no_cpu_baseline:
         import oracle
         oracle.lib()
@@ -399,6 +399,21 @@ def main():
             list(pool.map(one_layer, work))
             t_par = time.perf_counter() - t0
         del work
+        # the PEFT steps of one LoRA layer on the same oracle (one thread)
+        pflat_h = pflat.cpu().view(torch.int16).numpy().view(np.uint16)
+        t0 = time.perf_counter()
+        ppk_h = oracle.pack(pflat_h, pcfg.numel, pcfg.trainable, pcfg.G)
+        t_pack = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        oracle.unpack(ppk_h, pflat_h, pcfg.numel, pcfg.trainable)
+        t_unpack = time.perf_counter() - t0
+        pparts = [pgrads[r].cpu().numpy() for r in range(pcfg.G)]
+        t0 = time.perf_counter()
+        oracle.reduce(pparts, 0, pS, oracle.F32)
+        t_pred = time.perf_counter() - t0
+        cpu_peft = {"pack_us": round(t_pack * 1e6, 1), "unpack_us": round(t_unpack * 1e6, 1),
+                    "reduce_packed_us": round(t_pred * 1e6, 1), "cores": 1, "kind": "oracle"}
+        del pflat_h, ppk_h, pparts
         cpu_par = {"value": round(2 * n_t * layer_bytes / t_par / 1e9, 3), "unit": "GB/s",
                    "cores": n_t, "kind": "oracle, one layer per thread",
                    "sample": "%d layers at once, %.1f s wall" % (n_t, t_par)}
@@ -455,7 +470,7 @@ def main():
                  "unpack_us": round(unpack_us, 2), "reduce_packed_us": round(pred_us, 2),
                  "grad_shard_from_flat_grads_us": {"G_packs_then_reduce": round(unfused_us, 2),
                                                    "fused_reduce_trainable_shard": round(fused_us, 2)},
-                 "trainable_bytes": play.trainable_numel * 2,
+                 "trainable_bytes": play.trainable_numel * 2, "cpu_oracle": cpu_peft,
                  "whole_model_%d_layers" % wl: {"trainable_bytes": w_bytes, "pack_us": round(wpack_us, 2),
                                                 "unpack_us": round(wunpack_us, 2),
                                                 "pack_gbps": round(2 * w_bytes / (wpack_us * 1e-6) / 1e9, 1)}},
