@@ -33,7 +33,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 LINK_PEAK_GBPS = 63.0           # PCIe Gen5 x16 per direction, 128b/130b
 
 # HBM bytes per unflatten launch measured with rocprofv3 --pmc (FETCH_SIZE
-# x 1.99984, WRITE_SIZE x 1.0, the factors the same counters show for the
+# x 1.9998, WRITE_SIZE x 1.0, the factors the same counters show for the
 # plain copy of known size); profiles/unflatten_reduce_llama7b_g8_hbm_traffic.md
 MEASURED_TRAFFIC = {"llama7b_g8": 822.2e6, "llama7b_lora_g8": 823.3e6,
                     "llama13b_g16": 1288.7e6, "llama70b_g32": 3476.0e6}
