@@ -229,6 +229,35 @@ def test_bf16_rounding_all_upper_halves():
     assert np.array_equal(got[nan] >> 15, want[nan] >> 15)
 
 
+def test_bf16_rounding_all_lower_halves():
+    """The other direction of the test above: every one of the 65,536 lower
+    halves under 2,048 upper halves (both signs, all 256 exponents, the
+    mantissa patterns 0x00, 0x01, 0x7E, 0x7F: even and odd last kept bit, and
+    the carries into the exponent and into infinity).  The rounding decision
+    depends on the lower half and the last kept bit only, the carry on the
+    rest, so the two tests together cover every case of the 2^32 inputs."""
+    uppers = np.array([(s << 15) | (e << 7) | m for s in (0, 1) for e in range(256)
+                       for m in (0x00, 0x01, 0x7E, 0x7F)], dtype=np.uint32)
+    lows = np.arange(65536, dtype=np.uint32)
+    step = 256                                     # upper halves per chunk: 16.8 M inputs
+    d_out = torch.empty(step * 65536, dtype=torch.int16, device="cuda")
+    for c in range(0, uppers.size, step):
+        u = ((uppers[c:c + step, None] << 16) | lows[None, :]).reshape(-1)
+        x = u.view(np.float32)
+        want = oracle.bf16_rne(x)
+        d = to_dev(x)
+        torch.cuda.synchronize()
+        fcdp.fcdp_reduce_grad_shard([d], 1, 0, x.size, fcdp.F32, fcdp.BF16, d_out, None)
+        torch.cuda.synchronize()
+        got = d_out.cpu().numpy().view(np.uint16)
+        nan = (u & np.uint32(0x7FFFFFFF)) > np.uint32(0x7F800000)
+        assert np.array_equal(got[~nan], want[~nan]), c
+        if nan.any():
+            g = got[nan]
+            assert np.all((g & 0x7F80) == 0x7F80) and np.all((g & 0x7F) != 0), c
+            assert np.array_equal(g >> 15, want[nan] >> 15), c
+
+
 def test_reduce_in_place_and_all_ranks():
     """Every rank's shard in turn; the G shards concatenate to the full sum.
     Rank r reduces in place into its own partial's slice."""
