@@ -40,8 +40,9 @@
  *     must stay outside a capture.
  *   - Every data base pointer must be 16-byte aligned (FCDP_EALIGN if not).
  *     Offsets inside a buffer may be any element index.
- *   - Errors: a status code is returned, nothing is thrown and nothing
- *     aborts.  All argument checks precede the first enqueue, so a call that
+ *   - Errors: a status code is returned, nothing is thrown (every entry
+ *     point catches what its host code could throw, e.g. on exhausted host
+ *     memory, and returns FCDP_ENOMEM) and nothing aborts.  All argument checks precede the first enqueue, so a call that
  *     fails an argument check has no side effect.  fcdp_last_error() gives a
  *     thread-local text for the last failing call on the calling thread.
  *   - Zero-element tensors, N = 0 and N_t = 0 are legal no-ops.

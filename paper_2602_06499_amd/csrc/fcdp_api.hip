@@ -406,10 +406,12 @@ void fcdp_layout_destroy(fcdp_layout *L)
 }
 
 fcdp_status fcdp_layout_prepare(const fcdp_layout *L)
-{
+try {
     if (!L) return fail(FCDP_EINVAL, "fcdp_layout_prepare: layout is NULL");
     const fcdp::DeviceTables *d = nullptr;
     return tables_for_current_device(L, &d);
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_layout_prepare: out of host memory");
 }
 
 fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
@@ -417,7 +419,7 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
                                    void *host_cache, void *staging,
                                    void *const *tensor_ptrs, int store_cache,
                                    fcdp_stream compute_, fcdp_stream copy_)
-{
+try {
     const char *fn = "fcdp_materialize_layer";
     if (!L) return fail(FCDP_EINVAL, std::string(fn) + ": layout is NULL");
     if (src != FCDP_SRC_DEVICE_SHARDS && src != FCDP_SRC_HOST_DMA && src != FCDP_SRC_HOST_ZEROCOPY &&
@@ -525,11 +527,13 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *L, fcdp_source src,
                         reinterpret_cast<const void *const *>(tensor_ptrs), false, 0, compute,
                         "launch zero-copy unflatten", FCDP_KERNEL_UNFLATTEN_ZEROCOPY, tune.link_max_wgs,
                         tune.link_max_wgs > 0 ? tune.link_block : 0);
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_materialize_layer: out of host memory");
 }
 
 fcdp_status fcdp_flatten_to_shards(const fcdp_layout *L, const void *const *tensor_ptrs,
                                    void *const *shard_ptrs, fcdp_stream stream)
-{
+try {
     const char *fn = "fcdp_flatten_to_shards";
     if (!L) return fail(FCDP_EINVAL, std::string(fn) + ": layout is NULL");
     fcdp_status st = check_tensor_ptrs(L, tensor_ptrs, fn);
@@ -544,11 +548,13 @@ fcdp_status fcdp_flatten_to_shards(const fcdp_layout *L, const void *const *tens
     return run_windowed(L->flatten, tabs->flatten, fcdp::TensorSide::Src, L->T, small, L->G, tensor_ptrs,
                         tune.copy_nt != 0, tune.copy_wg_per_cu, static_cast<hipStream_t>(stream), "launch flatten",
                         FCDP_KERNEL_FLATTEN);
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_flatten_to_shards: out of host memory");
 }
 
 fcdp_status fcdp_cache_store(const fcdp_layout *L, const void *const *shard_ptrs, void *host_cache,
                              int store_mode, fcdp_stream compute_, fcdp_stream copy_)
-{
+try {
     const char *fn = "fcdp_cache_store";
     if (!L) return fail(FCDP_EINVAL, std::string(fn) + ": layout is NULL");
     if (store_mode != FCDP_STORE_DMA && store_mode != FCDP_STORE_ZEROCOPY)
@@ -564,10 +570,12 @@ fcdp_status fcdp_cache_store(const fcdp_layout *L, const void *const *shard_ptrs
     if ((st = current_ctx(&ctx)) != FCDP_OK) return st;
     return enqueue_store(L, ctx, shard_ptrs, host_cache, alias, store_mode,
                          static_cast<hipStream_t>(compute_), static_cast<hipStream_t>(copy_));
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_cache_store: out of host memory");
 }
 
 fcdp_status fcdp_link_bytes(int32_t reset, int64_t *stored, int64_t *fetched)
-{
+try {
     DeviceCtx *ctx = nullptr;
     fcdp_status st = current_ctx(&ctx);
     if (st != FCDP_OK) return st;
@@ -575,19 +583,23 @@ fcdp_status fcdp_link_bytes(int32_t reset, int64_t *stored, int64_t *fetched)
     if (fetched) *fetched = ctx->fetched_bytes;
     if (reset) ctx->stored_bytes = ctx->fetched_bytes = 0;
     return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_link_bytes: out of host memory");
 }
 
 fcdp_status fcdp_reduce_grad_shard(const void *const *partial_ptrs, int32_t G, int64_t elem_offset,
                                    int64_t count, fcdp_dtype in, fcdp_dtype out, void *out_shard,
                                    fcdp_stream stream)
-{
+try {
     return fcdp_reduce_grad_shard_scaled(partial_ptrs, G, elem_offset, count, in, out, 1.0f, out_shard, stream);
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_reduce_grad_shard: out of host memory");
 }
 
 fcdp_status fcdp_reduce_grad_shard_scaled(const void *const *partial_ptrs, int32_t G, int64_t elem_offset,
                                           int64_t count, fcdp_dtype in, fcdp_dtype out, float scale,
                                           void *out_shard, fcdp_stream stream)
-{
+try {
     const char *fn = "fcdp_reduce_grad_shard";
     if (!std::isfinite(scale)) return fail(FCDP_EINVAL, std::string(fn) + ": scale is not finite");
     if (!partial_ptrs) return fail(FCDP_EINVAL, std::string(fn) + ": partial_ptrs is NULL");
@@ -614,19 +626,23 @@ fcdp_status fcdp_reduce_grad_shard_scaled(const void *const *partial_ptrs, int32
                                                                count > 0 ? timing_events(FCDP_KERNEL_REDUCE) : fcdp::LaunchEvents()));
     if (e != hipSuccess) return hip_fail(e, "launch reduce");
     return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_reduce_grad_shard_scaled: out of host memory");
 }
 
 fcdp_status fcdp_reduce_trainable_shard(const fcdp_layout *L, const void *const *flat_grad_ptrs,
                                         int32_t rank, fcdp_dtype in, fcdp_dtype out, void *out_shard,
                                         fcdp_stream stream)
-{
+try {
     return fcdp_reduce_trainable_shard_scaled(L, flat_grad_ptrs, rank, in, out, 1.0f, out_shard, stream);
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_reduce_trainable_shard: out of host memory");
 }
 
 fcdp_status fcdp_reduce_trainable_shard_scaled(const fcdp_layout *L, const void *const *flat_grad_ptrs,
                                                int32_t rank, fcdp_dtype in, fcdp_dtype out, float scale,
                                                void *out_shard, fcdp_stream stream)
-{
+try {
     const char *fn = "fcdp_reduce_trainable_shard";
     if (!std::isfinite(scale)) return fail(FCDP_EINVAL, std::string(fn) + ": scale is not finite");
     if (!L) return fail(FCDP_EINVAL, std::string(fn) + ": layout is NULL");
@@ -672,6 +688,8 @@ fcdp_status fcdp_reduce_trainable_shard_scaled(const fcdp_layout *L, const void 
         if (e != hipSuccess) return hip_fail(e, "launch trainable reduce");
     }
     return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_reduce_trainable_shard_scaled: out of host memory");
 }
 
 static fcdp_status pack_or_unpack(const fcdp_layout *L, const void *src, void *dst, bool pack,
@@ -706,19 +724,23 @@ static fcdp_status pack_or_unpack(const fcdp_layout *L, const void *src, void *d
 }
 
 fcdp_status fcdp_pack_trainable(const fcdp_layout *L, const void *flat, void *packed, fcdp_stream stream)
-{
+try {
     return pack_or_unpack(L, flat, packed, true, stream, "fcdp_pack_trainable");
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_pack_trainable: out of host memory");
 }
 
 fcdp_status fcdp_unpack_trainable(const fcdp_layout *L, const void *packed, void *flat, fcdp_stream stream)
-{
+try {
     return pack_or_unpack(L, packed, flat, false, stream, "fcdp_unpack_trainable");
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_unpack_trainable: out of host memory");
 }
 
 // ------------------------------------------------------------- host cache
 
 fcdp_status fcdp_host_cache_alloc(size_t bytes, int numa_node, void **host, void **dev_alias)
-{
+try {
     const char *fn = "fcdp_host_cache_alloc";
     if (!host || !dev_alias) return fail(FCDP_EINVAL, std::string(fn) + ": NULL output pointer");
     *host = nullptr;
@@ -762,13 +784,17 @@ fcdp_status fcdp_host_cache_alloc(size_t bytes, int numa_node, void **host, void
     *dev_alias = d;
     fcdp::set_error(note);
     return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_host_cache_alloc: out of host memory");
 }
 
 fcdp_status fcdp_host_cache_free(void *host)
-{
+try {
     if (!host) return FCDP_OK;
     FCDP_HIP(hipHostFree(host), "hipHostFree");
     return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_host_cache_free: out of host memory");
 }
 
 // ------------------------------------------------------------ dirty state
@@ -785,7 +811,7 @@ struct fcdp_cache_state {
 extern "C" {
 
 fcdp_status fcdp_cache_state_create(int32_t n_layers, fcdp_cache_state **out)
-{
+try {
     if (!out) return fail(FCDP_EINVAL, "fcdp_cache_state_create: out is NULL");
     *out = nullptr;
     if (n_layers < 1) return fail(FCDP_EINVAL, "fcdp_cache_state_create: n_layers must be >= 1");
@@ -797,6 +823,8 @@ fcdp_status fcdp_cache_state_create(int32_t n_layers, fcdp_cache_state **out)
     s->resident.assign(static_cast<size_t>(n_layers), 0);
     *out = s;
     return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_cache_state_create: out of host memory");
 }
 
 void fcdp_cache_state_destroy(fcdp_cache_state *s) { delete s; }
@@ -808,7 +836,7 @@ static bool host_mode_ok(fcdp_source m)
 
 fcdp_status fcdp_cache_state_forward_source(fcdp_cache_state *s, int32_t layer, int32_t klass,
                                             fcdp_source host_mode, fcdp_source *src, int32_t *store_cache)
-{
+try {
     const char *fn = "fcdp_cache_state_forward_source";
     if (!s || !src || !store_cache) return fail(FCDP_EINVAL, std::string(fn) + ": NULL argument");
     if (layer < 0 || layer >= s->L || klass < 0 || klass > 1) return fail(FCDP_EINVAL, std::string(fn) + ": layer or class out of range");
@@ -824,11 +852,13 @@ fcdp_status fcdp_cache_state_forward_source(fcdp_cache_state *s, int32_t layer, 
         *store_cache = 0;
     }
     return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_cache_state_forward_source: out of host memory");
 }
 
 fcdp_status fcdp_cache_state_backward_source(const fcdp_cache_state *s, int32_t layer, int32_t klass,
                                              fcdp_source host_mode, fcdp_source *src)
-{
+try {
     const char *fn = "fcdp_cache_state_backward_source";
     if (!s || !src) return fail(FCDP_EINVAL, std::string(fn) + ": NULL argument");
     if (layer < 0 || layer >= s->L || klass < 0 || klass > 1) return fail(FCDP_EINVAL, std::string(fn) + ": layer or class out of range");
@@ -841,10 +871,12 @@ fcdp_status fcdp_cache_state_backward_source(const fcdp_cache_state *s, int32_t 
         return fail(FCDP_ESTATE, std::string(fn) + ": backward before the forward pass stored this layer");
     *src = host_mode;
     return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_cache_state_backward_source: out of host memory");
 }
 
 fcdp_status fcdp_cache_state_optimizer_step(fcdp_cache_state *s)
-{
+try {
     if (!s) return fail(FCDP_EINVAL, "fcdp_cache_state_optimizer_step: NULL state");
     for (int32_t l = 0; l < s->L; ++l) {
         s->dirty[static_cast<size_t>(l) * 2 + 1] = 1;
@@ -852,19 +884,23 @@ fcdp_status fcdp_cache_state_optimizer_step(fcdp_cache_state *s)
         s->resident[l] = 0;
     }
     return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_cache_state_optimizer_step: out of host memory");
 }
 
 fcdp_status fcdp_cache_state_set_tau(fcdp_cache_state *s, double tau)
-{
+try {
     if (!s) return fail(FCDP_EINVAL, "fcdp_cache_state_set_tau: NULL state");
     if (!(tau >= 0.0 && tau <= 1.0)) return fail(FCDP_EINVAL, "fcdp_cache_state_set_tau: tau must be in [0, 1]");
     s->tau = tau;
     return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_cache_state_set_tau: out of host memory");
 }
 
 fcdp_status fcdp_cache_state_place(fcdp_cache_state *s, int32_t layer, int64_t used_bytes,
                                    int64_t total_bytes, int32_t *keep)
-{
+try {
     const char *fn = "fcdp_cache_state_place";
     if (!s || !keep) return fail(FCDP_EINVAL, std::string(fn) + ": NULL argument");
     if (layer < 0 || layer >= s->L) return fail(FCDP_EINVAL, std::string(fn) + ": layer out of range");
@@ -880,14 +916,18 @@ fcdp_status fcdp_cache_state_place(fcdp_cache_state *s, int32_t layer, int64_t u
     s->resident[layer] = k ? 1 : 0;
     *keep = k ? 1 : 0;
     return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_cache_state_place: out of host memory");
 }
 
 fcdp_status fcdp_cache_state_release(fcdp_cache_state *s, int32_t layer)
-{
+try {
     if (!s) return fail(FCDP_EINVAL, "fcdp_cache_state_release: NULL state");
     if (layer < 0 || layer >= s->L) return fail(FCDP_EINVAL, "fcdp_cache_state_release: layer out of range");
     s->resident[layer] = 0;
     return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_cache_state_release: out of host memory");
 }
 
 int32_t fcdp_cache_state_is_dirty(const fcdp_cache_state *s, int32_t layer, int32_t klass)
@@ -899,7 +939,7 @@ int32_t fcdp_cache_state_is_dirty(const fcdp_cache_state *s, int32_t layer, int3
 // ----------------------------------------------------------------- tuning
 
 fcdp_status fcdp_tuning_set(const char *name, int64_t v)
-{
+try {
     if (!name) return fail(FCDP_EINVAL, "fcdp_tuning_set: name is NULL");
     fcdp::Tuning &t = fcdp::tuning();
     const std::string n(name);
@@ -941,6 +981,8 @@ fcdp_status fcdp_tuning_set(const char *name, int64_t v)
         return fail(FCDP_EINVAL, "fcdp_tuning_set: unknown knob " + n);
     }
     return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_tuning_set: out of host memory");
 }
 
 int64_t fcdp_tuning_get(const char *name)
@@ -963,7 +1005,7 @@ int64_t fcdp_tuning_get(const char *name)
 }
 
 fcdp_status fcdp_probe_copy(void *dst, const void *src, size_t bytes, fcdp_stream stream)
-{
+try {
     if (!dst || !src) return fail(FCDP_EINVAL, "fcdp_probe_copy: NULL buffer");
     if (!aligned16(dst) || !aligned16(src)) return fail(FCDP_EALIGN, "fcdp_probe_copy: buffer not 16-byte aligned");
     if (bytes & 1) return fail(FCDP_EINVAL, "fcdp_probe_copy: bytes must be even");
@@ -972,10 +1014,12 @@ fcdp_status fcdp_probe_copy(void *dst, const void *src, size_t bytes, fcdp_strea
     hipError_t e = static_cast<hipError_t>(fcdp::launch_plain_copy(dst, src, bytes, stream, shape));
     if (e != hipSuccess) return hip_fail(e, "launch plain copy");
     return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_probe_copy: out of host memory");
 }
 
 fcdp_status fcdp_timing_enable(int32_t capacity)
-{
+try {
     if (capacity < 0 || capacity > (1 << 20)) return fail(FCDP_EINVAL, "fcdp_timing_enable: capacity must be in 0..2^20");
     TimingCtx *c = timing_ctx();
     if (!c) return fail(FCDP_EHIP, "fcdp_timing_enable: no current device");
@@ -994,10 +1038,12 @@ fcdp_status fcdp_timing_enable(int32_t capacity)
     }
     c->on = true;
     return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_timing_enable: out of host memory");
 }
 
 fcdp_status fcdp_timing_collect(int32_t kind, int64_t *launches, double *total_ms)
-{
+try {
     if (!launches || !total_ms) return fail(FCDP_EINVAL, "fcdp_timing_collect: NULL output");
     *launches = 0;
     *total_ms = 0.0;
@@ -1018,6 +1064,8 @@ fcdp_status fcdp_timing_collect(int32_t kind, int64_t *launches, double *total_m
     c->taken.swap(keep);
     if (c->taken.empty()) c->next = 0; // every event is free again
     return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_timing_collect: out of host memory");
 }
 
 } // extern "C"

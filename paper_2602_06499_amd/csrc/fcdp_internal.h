@@ -72,6 +72,9 @@ namespace fcdp {
 void set_error(const std::string &msg);
 const std::string &last_error_ref();
 fcdp_status fail(fcdp_status st, const std::string &msg);
+// for catch-all handlers at the C boundary: records msg if that is possible
+// without throwing, and returns st
+fcdp_status fail_noexcept(fcdp_status st, const char *msg) noexcept;
 
 // tuning knobs (see fcdp_tuning_set)
 struct Tuning {

@@ -61,6 +61,16 @@ void index_windows(PieceTable &tab, TensorSide side, int32_t T)
 
 void set_error(const std::string &msg) { g_last_error = msg; }
 
+fcdp_status fail_noexcept(fcdp_status st, const char *msg) noexcept
+{
+    try {
+        g_last_error = msg;
+    } catch (...) {
+        g_last_error.clear(); // never throws
+    }
+    return st;
+}
+
 fcdp_status fail(fcdp_status st, const std::string &msg)
 {
     g_last_error = msg;
@@ -170,7 +180,7 @@ extern "C" {
 fcdp_status fcdp_layout_build(const int64_t *numel, const uint8_t *trainable,
                               int32_t n_tensors, int32_t G, int32_t elem_size,
                               int32_t pad_quantum, fcdp_layout **out)
-{
+try {
     if (!out) return fail(FCDP_EINVAL, "fcdp_layout_build: out is NULL");
     *out = nullptr;
     if (!numel) return fail(FCDP_EINVAL, "fcdp_layout_build: numel is NULL");
@@ -239,6 +249,8 @@ fcdp_status fcdp_layout_build(const int64_t *numel, const uint8_t *trainable,
     }
     *out = L;
     return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_layout_build: out of host memory");
 }
 
 int32_t fcdp_layout_n_tensors(const fcdp_layout *L) { return L ? L->T : -1; }
