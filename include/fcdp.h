@@ -137,7 +137,10 @@ int64_t fcdp_layout_segments(const fcdp_layout *layout, int64_t *rows,
 int64_t fcdp_layout_copy_plan(const fcdp_layout *layout, int32_t which,
                               int64_t *rows, int64_t cap);
 /* Uploads the layout's copy tables to the current device (synchronous,
- * idempotent).  Data calls do it on first use if it was not called. */
+ * idempotent) and, once per device, looks up the address of the library's
+ * static staging array and creates the events
+ * fcdp_materialize_layer_static uses.  Data calls other than that one do
+ * the upload on first use if it was not called. */
 fcdp_status fcdp_layout_prepare(const fcdp_layout *layout);
 
 /* ---------------------------------------------------- layer materialization
@@ -187,6 +190,36 @@ fcdp_status fcdp_materialize_layer(const fcdp_layout *layout, fcdp_source src,
                                    void *host_cache, void *staging,
                                    void *const *tensor_ptrs, int store_cache,
                                    fcdp_stream compute, fcdp_stream copy);
+
+/* The FCDP_SRC_HOST_DMA fetch for callers that cannot allocate device memory
+ * or pass a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  It does what fcdp_materialize_layer(layout,
+ * FCDP_SRC_HOST_DMA, NULL, host_cache, staging, tensor_ptrs, FCDP_STORE_NONE,
+ * compute, copy) does, with the staging buffer taken from a fixed array of
+ * FCDP_STATIC_STAGING_BYTES bytes that is part of the library's device image
+ * (every GPU the library runs on holds one until the process ends).  The call
+ * itself allocates nothing, uploads nothing and creates no event: the
+ * layout's tables, the array's address and the two events it uses are made by
+ * fcdp_layout_prepare, which must have been called for this layout on the
+ * current device (else FCDP_ESTATE).
+ *   host_cache   host ptr to N_pad*elem_size bytes of pinned memory
+ *   tensor_ptrs  host array of T dev ptrs, as for fcdp_materialize_layer
+ * Errors: N_pad*elem_size > FCDP_STATIC_STAGING_BYTES -> FCDP_ESIZE (nothing
+ * is enqueued); NULL / misaligned pointers as for fcdp_materialize_layer.
+ * The array needs no clearing: each call overwrites the N_pad*elem_size bytes
+ * it then reads, and bytes left by an earlier, larger layer are never read.
+ * All calls on one GPU share the array.  A call orders its copy after the
+ * previous call's scatter, so calls issued one after another from one thread
+ * (or serialised by the caller) are safe on any streams; calls issued
+ * concurrently from several threads on one GPU race on the array's contents
+ * and must be serialised by the caller.  The copy is not counted against
+ * max_copies_in_flight (it is at most FCDP_STATIC_STAGING_BYTES long). */
+#define FCDP_STATIC_STAGING_BYTES (32u << 20)
+fcdp_status fcdp_materialize_layer_static(const fcdp_layout *layout,
+                                          void *host_cache,
+                                          void *const *tensor_ptrs,
+                                          fcdp_stream compute,
+                                          fcdp_stream copy);
 
 /* The cache store alone (Alg. 1 "H[p] <- p"), for callers that decide after
  * the layer's forward computation whether to offload it (Sec. 4.4): copies

@@ -23,6 +23,7 @@ STORE_NONE = 0
 STORE_DMA = 1
 STORE_ZEROCOPY = 2
 MAX_G = 64
+STATIC_STAGING_BYTES = 32 << 20
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfcdp.so")
@@ -40,7 +41,8 @@ EXPORTS = [
     "fcdp_layout_trainable_numel", "fcdp_layout_packed_numel",
     "fcdp_layout_offsets", "fcdp_layout_segments", "fcdp_layout_copy_plan",
     "fcdp_layout_prepare",
-    "fcdp_materialize_layer", "fcdp_cache_store", "fcdp_flatten_to_shards",
+    "fcdp_materialize_layer", "fcdp_materialize_layer_static",
+    "fcdp_cache_store", "fcdp_flatten_to_shards",
     "fcdp_reduce_grad_shard", "fcdp_reduce_trainable_shard",
     "fcdp_reduce_grad_shard_scaled", "fcdp_reduce_trainable_shard_scaled",
     "fcdp_pack_trainable", "fcdp_unpack_trainable",
@@ -99,6 +101,7 @@ def load_library() -> ctypes.CDLL:
     lib.fcdp_layout_copy_plan.restype = i64
     lib.fcdp_layout_prepare.argtypes = [vp]
     lib.fcdp_materialize_layer.argtypes = [vp, c.c_int, vp, vp, vp, vp, c.c_int, vp, vp]
+    lib.fcdp_materialize_layer_static.argtypes = [vp, vp, vp, vp, vp]
     lib.fcdp_flatten_to_shards.argtypes = [vp, vp, vp, vp]
     lib.fcdp_cache_store.argtypes = [vp, vp, vp, c.c_int, vp, vp]
     lib.fcdp_cache_state_set_tau.argtypes = [vp, c.c_double]
@@ -247,6 +250,13 @@ def fcdp_materialize_layer(layout: Layout, src: int, shard_ptrs, host_cache,
     _check(load_library().fcdp_materialize_layer(
         layout.handle, src, _ptr_array(shard_ptrs), _ptr(host_cache),
         _ptr(staging), _ptr_array(tensor_ptrs), int(store_cache),
+        _stream(compute), _stream(copy)))
+
+
+def fcdp_materialize_layer_static(layout: Layout, host_cache, tensor_ptrs,
+                                  compute=None, copy=None) -> None:
+    _check(load_library().fcdp_materialize_layer_static(
+        layout.handle, _ptr(host_cache), _ptr_array(tensor_ptrs),
         _stream(compute), _stream(copy)))
 
 

@@ -17,6 +17,14 @@
 
 using fcdp::fail;
 
+// fcdp_materialize_layer_static stages the host-cache image in this array
+// instead of a caller-provided staging buffer.  Every device the library
+// runs on holds its own copy of the array, at its own address, from the
+// moment the code object is loaded until the process ends.  In host code the
+// name is only a handle for hipGetSymbolAddress; kernels and copies get the
+// address that call returns (StaticCtx::ptr below).
+static __device__ __align__(256) unsigned char scratch[FCDP_STATIC_STAGING_BYTES];
+
 namespace {
 
 fcdp_status hip_fail(hipError_t e, const char *what)
@@ -385,6 +393,52 @@ fcdp_status enqueue_store(const fcdp_layout *L, DeviceCtx *ctx, const void *cons
     return FCDP_OK;
 }
 
+
+// ------------------------------------------- allocation-free staged fetch
+
+// Per device: the array's device address (the array's name is only a
+// host-side handle for hipGetSymbolAddress, never a device address), and the
+// two events the entry point needs, all made once at set-up
+// (fcdp_layout_prepare) so that the entry point itself creates nothing.
+struct StaticCtx {
+    std::mutex mu;
+    void *ptr = nullptr;          // device address of `scratch` on this device
+    hipEvent_t copied = nullptr;  // the H2D copy into the array has finished
+    hipEvent_t read_done = nullptr; // the last scatter that read the array has finished
+    bool read_recorded = false;
+    bool ready = false;
+};
+StaticCtx g_static[fcdp::kMaxDevices];
+
+// Set-up for the current device; idempotent.
+fcdp_status static_setup_current_device()
+{
+    int dev = 0;
+    FCDP_HIP(hipGetDevice(&dev), "hipGetDevice");
+    if (dev < 0 || dev >= fcdp::kMaxDevices)
+        return fail(FCDP_ESIZE, "device ordinal beyond 15 is not supported");
+    StaticCtx &c = g_static[dev];
+    std::lock_guard<std::mutex> lk(c.mu);
+    if (c.ready) return FCDP_OK;
+    void *p = nullptr;
+    FCDP_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+    if (!p || !aligned16(p)) return fail(FCDP_EHIP, "hipGetSymbolAddress(scratch) gave an unusable address");
+    if (!c.copied) FCDP_HIP(hipEventCreateWithFlags(&c.copied, hipEventDisableTiming), "hipEventCreate");
+    if (!c.read_done) FCDP_HIP(hipEventCreateWithFlags(&c.read_done, hipEventDisableTiming), "hipEventCreate");
+    c.ptr = p;
+    c.ready = true;
+    return FCDP_OK;
+}
+
+// The layout's tables on the current device if they were uploaded, else NULL.
+const fcdp::DeviceTables *tables_if_prepared(const fcdp_layout *L, int dev)
+{
+    std::lock_guard<std::mutex> lk(L->mu);
+    for (const auto &d : L->dev)
+        if (d.device == dev) return &d;
+    return nullptr;
+}
+
 } // namespace
 
 extern "C" {
@@ -409,7 +463,9 @@ fcdp_status fcdp_layout_prepare(const fcdp_layout *L)
 try {
     if (!L) return fail(FCDP_EINVAL, "fcdp_layout_prepare: layout is NULL");
     const fcdp::DeviceTables *d = nullptr;
-    return tables_for_current_device(L, &d);
+    fcdp_status st = tables_for_current_device(L, &d);
+    if (st != FCDP_OK) return st;
+    return static_setup_current_device();
 } catch (...) {
     return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_layout_prepare: out of host memory");
 }
@@ -529,6 +585,57 @@ try {
                         tune.link_max_wgs > 0 ? tune.link_block : 0);
 } catch (...) {
     return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_materialize_layer: out of host memory");
+}
+
+fcdp_status fcdp_materialize_layer_static(const fcdp_layout *L, void *host_cache,
+                                          void *const *tensor_ptrs, fcdp_stream compute_,
+                                          fcdp_stream copy_)
+try {
+    const char *fn = "fcdp_materialize_layer_static";
+    if (!L) return fail(FCDP_EINVAL, std::string(fn) + ": layout is NULL");
+    fcdp_status st = check_tensor_ptrs(L, reinterpret_cast<const void *const *>(tensor_ptrs), fn);
+    if (st != FCDP_OK) return st;
+    if (!host_cache) return fail(FCDP_EINVAL, std::string(fn) + ": host_cache is NULL");
+    if (!aligned16(host_cache)) return fail(FCDP_EALIGN, std::string(fn) + ": host_cache is not 16-byte aligned");
+    const size_t flat_bytes = static_cast<size_t>(L->N_pad) * L->esz;
+    const size_t shard_bytes = static_cast<size_t>(L->S) * L->esz;
+    if (flat_bytes > FCDP_STATIC_STAGING_BYTES)
+        return fail(FCDP_ESIZE, std::string(fn) + ": the padded layer (" + std::to_string(flat_bytes) +
+                                    " bytes) exceeds FCDP_STATIC_STAGING_BYTES (" +
+                                    std::to_string(static_cast<size_t>(FCDP_STATIC_STAGING_BYTES)) + ")");
+    if (L->N == 0) return FCDP_OK;
+    int dev = 0;
+    FCDP_HIP(hipGetDevice(&dev), "hipGetDevice");
+    if (dev < 0 || dev >= fcdp::kMaxDevices)
+        return fail(FCDP_ESIZE, "device ordinal beyond 15 is not supported");
+    StaticCtx &c = g_static[dev];
+    const fcdp::DeviceTables *tabs = tables_if_prepared(L, dev);
+    if (!tabs || !c.ready)
+        return fail(FCDP_ESTATE, std::string(fn) + ": call fcdp_layout_prepare for this layout on this device first "
+                                                   "(this entry point uploads and allocates nothing)");
+    hipStream_t compute = static_cast<hipStream_t>(compute_);
+    hipStream_t copy = static_cast<hipStream_t>(copy_);
+    const fcdp::Tuning &tune = fcdp::tuning();
+    std::lock_guard<std::mutex> lk(c.mu);
+    // the array may still be read by the scatter of the previous call
+    if (c.read_recorded) FCDP_HIP(hipStreamWaitEvent(copy, c.read_done, 0), "hipStreamWaitEvent(scratch)");
+    FCDP_HIP(hipMemcpyAsync(c.ptr, host_cache, flat_bytes, hipMemcpyHostToDevice, copy), "hipMemcpyAsync(H2D)");
+    if (copy != compute) {
+        FCDP_HIP(hipEventRecord(c.copied, copy), "hipEventRecord");
+        FCDP_HIP(hipStreamWaitEvent(compute, c.copied, 0), "hipStreamWaitEvent");
+    }
+    const void *small[FCDP_MAX_G];
+    for (int32_t r = 0; r < L->G; ++r) small[r] = static_cast<const char *>(c.ptr) + r * shard_bytes;
+    st = run_windowed(L->unflatten, tabs->unflatten, fcdp::TensorSide::Dst, L->T, small, L->G,
+                      reinterpret_cast<const void *const *>(tensor_ptrs), tune.copy_nt != 0,
+                      tune.copy_wg_per_cu, compute, "launch unflatten", FCDP_KERNEL_UNFLATTEN);
+    if (st != FCDP_OK) return st;
+    FCDP_HIP(hipEventRecord(c.read_done, compute), "hipEventRecord(scratch)");
+    c.read_recorded = true;
+    g_ctx[dev].fetched_bytes += static_cast<int64_t>(flat_bytes);
+    return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_materialize_layer_static: out of host memory");
 }
 
 fcdp_status fcdp_flatten_to_shards(const fcdp_layout *L, const void *const *tensor_ptrs,

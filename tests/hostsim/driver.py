@@ -87,6 +87,12 @@ def check_layer(name, sizes, G, esz, offset):
                                     fcdp.STORE_NONE, STREAM_A, STREAM_B)
         for t, w in enumerate(want):
             assert np.array_equal(outs[t].view(dt), w), (name, mode, t)
+    if Np * esz <= fcdp.STATIC_STAGING_BYTES:
+        # the allocation-free staged fetch: same tensors out of the static array
+        outs = [Buf(k * esz, offset) for k in sizes]
+        fcdp.fcdp_materialize_layer_static(L, H, outs, STREAM_A, STREAM_B)
+        for t, w in enumerate(want):
+            assert np.array_equal(outs[t].view(dt), w), (name, "static", t)
     H.free()
     L.destroy()
 

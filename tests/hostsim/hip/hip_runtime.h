@@ -17,6 +17,9 @@ extern thread_local dim3 threadIdx, blockIdx, blockDim, gridDim;
 #define __forceinline__ inline
 #define __launch_bounds__(x)
 #define __restrict__
+#define __align__(n) __attribute__((aligned(n)))
+#define HIP_SYMBOL(x) (&(x))
+static inline int hipGetSymbolAddress(void **p, const void *sym) { *p = const_cast<void *>(sym); return 0; }
 #define __builtin_amdgcn_readfirstlane(v) (v)
 static inline uint32_t __float_as_uint(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
 static inline float __uint_as_float(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
