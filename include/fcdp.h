@@ -402,7 +402,17 @@ const char *fcdp_last_error(void);
  *   copy_unroll           16-byte vectors in flight per lane: 1, 2, 4, 8 (1)
  *   copy_nt               non-temporal hint, bit 0 loads, bit 1 stores (3)
  *   copy_wg_per_cu        cap on workgroups per compute unit, 0 = none (0)
- *   reduce_block          threads per workgroup of the reduce, 64..256 (64)
+ *   reduce_block          threads per workgroup of the one-tile-per-workgroup
+ *                         reduce kernel, 64..256 (64)
+ *   reduce_phased         which reduce kernel runs: 0 one tile per workgroup,
+ *                         stored as soon as it is summed; 1 the phased kernel
+ *                         (a persistent grid whose waves keep their sums in
+ *                         registers and store them after their last load, so
+ *                         that the chip reads, then writes) whenever slices
+ *                         and output are 16-byte aligned and at least 8 steps
+ *                         per wave long; 2 the phased kernel where it measured
+ *                         faster: G >= 12, or fp32 in and out with G >= 3 (2).
+ *                         The result is the same bits either way.
  *   link_max_wgs          workgroups of the zero-copy fetch / store kernels,
  *                         0 = no bound (64)
  *   link_block            their threads per workgroup (256)

@@ -1081,6 +1081,9 @@ try {
     } else if (n == "reduce_block") {
         if (v < 64 || v > 256 || !pow2(v)) return fail(FCDP_EINVAL, "reduce_block: power of two in 64..256");
         t.reduce_block = v;
+    } else if (n == "reduce_phased") {
+        if (v < 0 || v > 2) return fail(FCDP_EINVAL, "reduce_phased: 0, 1 or 2");
+        t.reduce_phased = v;
     } else if (n == "debug_poison") {
         if (v != 0 && v != 1) return fail(FCDP_EINVAL, "debug_poison: 0 or 1");
         t.debug_poison = v;
@@ -1107,6 +1110,7 @@ int64_t fcdp_tuning_get(const char *name)
     if (n == "copy_nt") return t.copy_nt;
     if (n == "max_copies_in_flight") return t.max_copies_in_flight;
     if (n == "reduce_block") return t.reduce_block;
+    if (n == "reduce_phased") return t.reduce_phased;
     if (n == "debug_poison") return t.debug_poison;
     return -1;
 }

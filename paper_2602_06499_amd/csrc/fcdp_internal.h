@@ -98,6 +98,12 @@ struct Tuning {
     // to 20-30 GB/s.  2 is also the depth double buffering needs.  0 = off
     int64_t max_copies_in_flight = 2;
     int64_t reduce_block = 64;
+    // The phased reduce (persistent waves keep their sums in registers and
+    // store them after the last load of a phase) against one tile per
+    // workgroup, stored as soon as it is summed: 0 never phased, 1 phased
+    // whenever the slices are 16-byte aligned and long enough, 2 phased where
+    // it measured faster (by G and the two element types)
+    int64_t reduce_phased = 2;
     // debugging aid, off by default (the environment variable FCDP_DEBUG_POISON=1
     // turns it on at load): outputs are filled with kPoison before the work that
     // writes them is enqueued, so a consumer that misses a wait reads poison

@@ -242,6 +242,9 @@ struct ReduceArgs {
     int64_t count;
     int32_t G;
     float scale; // multiplies the finished sum; 1.0f leaves every value as it is
+    // reduce_phased only: a wave runs `phases` phases of at most `spp` steps
+    int32_t phases;
+    int32_t spp;
 };
 
 __device__ __forceinline__ uint32_t bf16_rne_bits(float x)
@@ -384,6 +387,176 @@ __global__ void __launch_bounds__(256) reduce_ranks(const ReduceArgs a)
     }
     // the last count % 4 elements, one thread each
     const int64_t k = (nvec << 2) + threadIdx.x;
+    if (blockIdx.x == 0 && k < a.count) {
+        float acc = -0.0f;
+        for (int g = 0; g < a.G; ++g) {
+            float v;
+            if constexpr (IN_F32)
+                v = reinterpret_cast<const float *>(a.p[g])[k];
+            else
+                v = __uint_as_float(static_cast<uint32_t>(
+                        reinterpret_cast<const uint16_t *>(a.p[g])[k]) << 16);
+            acc = acc + v;
+        }
+        acc = acc * a.scale;
+        if constexpr (OUT_F32)
+            reinterpret_cast<float *>(a.out)[k] = acc;
+        else
+            reinterpret_cast<uint16_t *>(a.out)[k] =
+                static_cast<uint16_t>(bf16_rne_bits(acc));
+    }
+}
+
+// ---- phased reduce: reads and writes kept apart in time -------------------
+// Measured on MI355X: a read stream of G partials runs at 7.0 TB/s, and the
+// same stream with the output written as it is produced at 6.0 TB/s, although
+// the output is only 3-11 % of the bytes: stores that trickle into a
+// read-dominated stream cost the memory system far more than their bytes.
+// Here the whole chip reads for a while and then writes for a while.  The
+// grid is persistent: two waves per SIMD, all resident at once, and every
+// wave owns one contiguous run of steps (a step = 64 lanes x one 4-element
+// vector).  A wave sums up to kPhaseSteps steps of every partial, keeps the
+// finished sums in registers (4 per step and lane) and stores them only
+// after its last load of the phase.  All waves have the same work, so they
+// reach their stores at about the same time and the stores arrive at the
+// memory as one burst.  With kPhaseSteps = 52 one phase holds 2048 waves x
+// 52 KiB = 109 MB of fp32 sums on a 256-CU part, i.e. the whole shard of
+// every Llama-shaped layer here; longer inputs take several phases.  Giving
+// each wave a contiguous run (rather than dealing steps round robin) and
+// holding more steps per wave both measured faster: 16 steps at four waves
+// per SIMD reaches 6.4 TB/s at G = 32, 48 steps at two waves 6.8 TB/s.
+// The adds per element stay in rank order, one wave and lane owns an element
+// from its first load to its store, and the launch shape changes nothing in
+// the result.
+#ifndef FCDP_PHASE_STEPS
+#define FCDP_PHASE_STEPS 52
+#endif
+#ifndef FCDP_PHASE_WAVES_PER_EU
+#define FCDP_PHASE_WAVES_PER_EU 2
+#endif
+constexpr int kPhaseSteps = FCDP_PHASE_STEPS;              // steps of 4 elements per lane held per phase
+constexpr int kPhasedBlock = 256;                          // four waves
+constexpr int kPhasedWavesPerSimd = FCDP_PHASE_WAVES_PER_EU;
+constexpr int kPhasedMinStepsPerWave = 8; // below this the one-tile-per-workgroup kernel is used
+#ifndef FCDP_PHASE_GROUP
+#define FCDP_PHASE_GROUP 8
+#endif
+constexpr int kPhasedGroup = FCDP_PHASE_GROUP; // partials loaded back to back before their adds
+
+// One lane's share of a step: 16 bytes of one partial = E elements (4 fp32
+// or 8 bf16), widened to fp32 only when they are added, so that the loads of
+// a group wait in 4 registers each.
+template <bool IN_F32>
+__device__ __forceinline__ void widen_unit(const u32x4 r, float (&v)[IN_F32 ? 4 : 8])
+{
+    if constexpr (IN_F32) {
+        v[0] = __uint_as_float(r.x);
+        v[1] = __uint_as_float(r.y);
+        v[2] = __uint_as_float(r.z);
+        v[3] = __uint_as_float(r.w);
+    } else {
+        v[0] = __uint_as_float(r.x << 16);
+        v[1] = __uint_as_float(r.x & 0xffff0000u);
+        v[2] = __uint_as_float(r.y << 16);
+        v[3] = __uint_as_float(r.y & 0xffff0000u);
+        v[4] = __uint_as_float(r.z << 16);
+        v[5] = __uint_as_float(r.z & 0xffff0000u);
+        v[6] = __uint_as_float(r.w << 16);
+        v[7] = __uint_as_float(r.w & 0xffff0000u);
+    }
+}
+
+// Stores one lane's E finished sums: E * 4 bytes (fp32) or E * 2 bytes (bf16).
+// Plain stores: with all stores of the chip in one burst they measured 1-2 %
+// faster than non-temporal ones.
+template <bool OUT_F32, int E>
+__device__ __forceinline__ void store_unit(char *out, int64_t unit, const float (&a)[E])
+{
+    if constexpr (OUT_F32) {
+#pragma unroll
+        for (int h = 0; h < E / 4; ++h)
+            store16<false>(out + unit * (E * 4) + h * 16,
+                           u32x4{__float_as_uint(a[4 * h]), __float_as_uint(a[4 * h + 1]),
+                                 __float_as_uint(a[4 * h + 2]), __float_as_uint(a[4 * h + 3])});
+    } else if constexpr (E == 8) {
+        store16<false>(out + unit * 16,
+                       u32x4{bf16_rne_bits(a[0]) | (bf16_rne_bits(a[1]) << 16),
+                             bf16_rne_bits(a[2]) | (bf16_rne_bits(a[3]) << 16),
+                             bf16_rne_bits(a[4]) | (bf16_rne_bits(a[5]) << 16),
+                             bf16_rne_bits(a[6]) | (bf16_rne_bits(a[7]) << 16)});
+    } else {
+        *reinterpret_cast<u32x2 *>(out + unit * 8) =
+            u32x2{bf16_rne_bits(a[0]) | (bf16_rne_bits(a[1]) << 16),
+                  bf16_rne_bits(a[2]) | (bf16_rne_bits(a[3]) << 16)};
+    }
+}
+
+// Adds partials g0 .. g0+K-1 of one unit to acc in that order; the K loads
+// are issued before the first add.
+template <int K, bool IN_F32, bool NT>
+__device__ __forceinline__ void add_group1(const ReduceArgs &a, int g0, int64_t unit,
+                                           float (&acc)[IN_F32 ? 4 : 8])
+{
+    constexpr int E = IN_F32 ? 4 : 8;
+    u32x4 r[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) r[k] = load16<16, NT>(a.p[g0 + k] + unit * 16);
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        float v[E];
+        widen_unit<IN_F32>(r[k], v);
+#pragma unroll
+        for (int c = 0; c < E; ++c) acc[c] = acc[c] + v[c];
+    }
+}
+
+// Needs 16-byte aligned input slices and output (the launcher falls back to
+// reduce_ranks otherwise).  A unit is 16 bytes of input = E elements; a step
+// is 64 units, one per lane; a wave holds up to STEPS = kPhaseSteps * 4 / E
+// steps, i.e. kPhaseSteps * 4 sums per lane whatever the input type.
+template <int REM, bool IN_F32, bool OUT_F32, bool NT>
+__global__ void __launch_bounds__(kPhasedBlock, FCDP_PHASE_WAVES_PER_EU) // threads, waves per SIMD
+reduce_phased(const ReduceArgs a)
+{
+    constexpr int E = IN_F32 ? 4 : 8;
+    constexpr int STEPS = kPhaseSteps * 4 / E;
+    const int64_t n_units = a.count / E;
+    const int64_t n_steps = (n_units + 63) >> 6;
+    const int64_t w = static_cast<int64_t>(blockIdx.x) * (kPhasedBlock / 64) +
+                      __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
+    const int lane = static_cast<int>(threadIdx.x & 63u);
+    const int full = a.G - REM; // REM = G mod kPhasedGroup
+    for (int p = 0; p < a.phases; ++p) {
+        // this wave's run of the phase: steps [s0, s0 + spp)
+        const int64_t s0 = (w * a.phases + p) * a.spp;
+        float acc[STEPS][E];
+#pragma unroll
+        for (int j = 0; j < STEPS; ++j) {
+            const int64_t s = s0 + j;
+            if (j < a.spp && s < n_steps) { // the same for every lane of the wave
+                const int64_t idx = (s << 6) + lane;
+                // the last step may be partial: clamp the load index, skip the store
+                const int64_t lidx = idx < n_units ? idx : n_units - 1;
+#pragma unroll
+                for (int c = 0; c < E; ++c) acc[j][c] = -0.0f; // the identity of IEEE addition, also for -0
+                for (int g = 0; g < full; g += kPhasedGroup)
+                    add_group1<kPhasedGroup, IN_F32, NT>(a, g, lidx, acc[j]);
+                if constexpr (REM > 0) add_group1<REM, IN_F32, NT>(a, full, lidx, acc[j]);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < STEPS; ++j) {
+            const int64_t s = s0 + j;
+            if (j < a.spp && s < n_steps) {
+                const int64_t idx = (s << 6) + lane;
+#pragma unroll
+                for (int c = 0; c < E; ++c) acc[j][c] = acc[j][c] * a.scale;
+                if (idx < n_units) store_unit<OUT_F32, E>(a.out, idx, acc[j]);
+            }
+        }
+    }
+    // the last count % E elements, one thread each
+    const int64_t k = n_units * E + threadIdx.x;
     if (blockIdx.x == 0 && k < a.count) {
         float acc = -0.0f;
         for (int g = 0; g < a.G; ++g) {
@@ -554,6 +727,32 @@ hipError_t launch_reduce_r(const ReduceArgs &args, dim3 grid, dim3 block, hipStr
 {
     return launch_one(reduce_ranks<REM, IN_F32, OUT_F32, ALIGNED, kReduceUnroll, kReduceNT>,
                       grid, block, st, ev, args);
+}
+
+template <int REM, bool IN_F32, bool OUT_F32>
+hipError_t launch_phased_r(const ReduceArgs &args, dim3 grid, dim3 block, hipStream_t st,
+                           const LaunchEvents &ev)
+{
+    if constexpr (REM < kPhasedGroup)
+        return launch_one(reduce_phased<REM, IN_F32, OUT_F32, kReduceNT>, grid, block, st, ev, args);
+    else
+        return hipErrorInvalidValue; // not reachable: REM = G mod kPhasedGroup
+}
+
+template <bool IN_F32, bool OUT_F32>
+hipError_t launch_phased_t(const ReduceArgs &args, dim3 grid, dim3 block, hipStream_t st,
+                           const LaunchEvents &ev)
+{
+    switch (args.G % kPhasedGroup) {
+    case 0: return launch_phased_r<0, IN_F32, OUT_F32>(args, grid, block, st, ev);
+    case 1: return launch_phased_r<1, IN_F32, OUT_F32>(args, grid, block, st, ev);
+    case 2: return launch_phased_r<2, IN_F32, OUT_F32>(args, grid, block, st, ev);
+    case 3: return launch_phased_r<3, IN_F32, OUT_F32>(args, grid, block, st, ev);
+    case 4: return launch_phased_r<4, IN_F32, OUT_F32>(args, grid, block, st, ev);
+    case 5: return launch_phased_r<5, IN_F32, OUT_F32>(args, grid, block, st, ev);
+    case 6: return launch_phased_r<6, IN_F32, OUT_F32>(args, grid, block, st, ev);
+    default: return launch_phased_r<7, IN_F32, OUT_F32>(args, grid, block, st, ev);
+    }
 }
 
 template <bool IN_F32, bool OUT_F32, bool ALIGNED>
@@ -731,13 +930,37 @@ int launch_reduce(const void *const *partials, int32_t G, int64_t elem_offset,
     args.G = G;
     args.scale = scale;
     const Tuning &t = tuning();
-    const int64_t block = t.reduce_block;
     const int64_t nvec = count >> 2;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool inf = in_dtype == FCDP_F32, outf = out_dtype == FCDP_F32;
+    // the persistent grid: every wave resident at once
+    const int64_t wpb = kPhasedBlock / 64;
+    const int64_t epu = inf ? 4 : 8;                       // elements per 16-byte unit
+    const int64_t steps_cap = kPhaseSteps * 4 / epu;       // steps a wave holds per phase
+    const int64_t n_steps = (count / epu + 63) / 64;
+    const int64_t W = static_cast<int64_t>(device_cu_count()) * 4 * kPhasedWavesPerSimd;
+    // Where it pays (30 launches each on MI355X, a 25 M-element shard, G = 1..64,
+    // all four type pairs): fp32 partials into an fp32 shard from G = 3 on
+    // (+1 to +9 % of the HBM peak), every other type pair from G = 12 on (+1
+    // to +5 %); below that the one-tile-per-workgroup kernel is 1-4 % faster.
+    const bool pays = t.reduce_phased == 1 || (t.reduce_phased == 2 && (G >= 12 || (G >= 3 && inf && outf)));
+    if (pays && aligned && (reinterpret_cast<uintptr_t>(out) & 15u) == 0 &&
+        n_steps >= W * kPhasedMinStepsPerWave) {
+        const int64_t phases = (n_steps + W * steps_cap - 1) / (W * steps_cap);
+        if (phases > 0x7fffffff) return hipErrorInvalidValue;
+        args.phases = static_cast<int32_t>(phases);
+        args.spp = static_cast<int32_t>((n_steps + W * phases - 1) / (W * phases)); // <= steps_cap
+        const dim3 g(static_cast<unsigned>(W / wpb)), b(kPhasedBlock);
+        if (inf && outf) return launch_phased_t<true, true>(args, g, b, st, ev);
+        if (inf && !outf) return launch_phased_t<true, false>(args, g, b, st, ev);
+        if (!inf && outf) return launch_phased_t<false, true>(args, g, b, st, ev);
+        return launch_phased_t<false, false>(args, g, b, st, ev);
+    }
+    args.phases = args.spp = 0;
+    const int64_t block = t.reduce_block;
     int64_t grid = (nvec + block * kReduceUnroll - 1) / (block * kReduceUnroll);
     grid = std::max<int64_t>(1, std::min<int64_t>(grid, 0x7fffffff));
     const dim3 g(static_cast<unsigned>(grid)), b(static_cast<unsigned>(block));
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const bool inf = in_dtype == FCDP_F32, outf = out_dtype == FCDP_F32;
     if (inf && outf)
         return aligned ? launch_reduce_t<true, true, true>(args, g, b, st, ev)
                        : launch_reduce_t<true, true, false>(args, g, b, st, ev);

@@ -208,7 +208,11 @@ def main():
     reduce_cases = [(1, 1000, 0), (2, 4099, 0), (3, 7001, 5), (7, 3333, 3),
                     (8, 30007, 0), (9, 1234, 1), (15, 5000, 2), (16, 6553, 0),
                     (17, 4000, 7), (33, 2049, 0), (64, 3001, 11), (5, 3, 0),
-                    (5, 0, 0)]
+                    (5, 0, 0),
+                    # the phased reduce (aligned slices of at least 8 steps per wave; the
+                    # stand-in device has 4 compute units = 32 waves x 52 steps x 256
+                    # elements per phase): one phase, two phases, and the unaligned fallback
+                    (9, 270001, 0), (3, 600007, 0), (3, 600007, 1), (2, 66000, 4)]
     for G, count, e0 in reduce_cases:
         for in_dt, out_dt in ((oracle.F32, oracle.F32), (oracle.F32, oracle.BF16),
                               (oracle.BF16, oracle.BF16), (oracle.BF16, oracle.F32)):

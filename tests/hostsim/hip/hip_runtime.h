@@ -15,7 +15,7 @@ extern thread_local dim3 threadIdx, blockIdx, blockDim, gridDim;
 #define __global__
 #define __device__
 #define __forceinline__ inline
-#define __launch_bounds__(x)
+#define __launch_bounds__(...)
 #define __restrict__
 #define __align__(n) __attribute__((aligned(n)))
 #define HIP_SYMBOL(x) (&(x))

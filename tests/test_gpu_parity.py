@@ -277,6 +277,126 @@ def test_reduce_in_place_and_all_ranks():
     arena.check_guards()
 
 
+# The phased reduce (persistent waves that keep their sums in registers and
+# store them after their last load) only runs on aligned slices of at least 8
+# steps per wave (4.2 M fp32 / 8.4 M bf16 elements on 256 compute units), so
+# the small cases above never reach it.  Counts here sit just above that
+# threshold, with ragged tails (count % 4, a partial last step), every
+# remainder of G modulo the load group, and, for G = 2, more than one phase
+# (beyond 27.3 M elements).
+PHASED_CASES = [
+    # G, count, elem_offset, in, out, knob
+    (1, 4194304, 0, oracle.F32, oracle.F32, 1),          # exactly 8 steps per wave
+    (2, 4194304 + 255, 0, oracle.F32, oracle.BF16, 1),   # partial last step, count % 4 = 3
+    (3, 4300001, 4, oracle.F32, oracle.F32, 2),          # auto rule takes it (fp32 in and out, G >= 3)
+    (5, 4200002, 8, oracle.F32, oracle.F32, 2),
+    (8, 4194304 + 64 * 4 * 7 + 2, 0, oracle.F32, oracle.F32, 2),
+    (9, 4250000, 12, oracle.F32, oracle.BF16, 1),
+    (12, 4200003, 0, oracle.F32, oracle.BF16, 2),        # auto rule takes every type pair from G = 12
+    (15, 4194304 + 1, 0, oracle.F32, oracle.F32, 2),
+    (23, 4210000, 16, oracle.BF16, oracle.F32, 1),       # bf16 in needs 8.4 M elements: falls back
+    (16, 8388608 + 517, 8, oracle.BF16, oracle.BF16, 2), # bf16 in, 8 elements per lane and step
+    (13, 8400007, 0, oracle.BF16, oracle.F32, 2),
+    (7, 8388608 + 9, 16, oracle.BF16, oracle.BF16, 1),
+    (32, 4300000, 0, oracle.F32, oracle.BF16, 2),
+    (64, 4194304 + 260, 0, oracle.F32, oracle.F32, 2),
+    (2, 27262976 + 300001, 0, oracle.F32, oracle.F32, 1),   # two phases
+    (2, 3 * 27262976 + 77, 0, oracle.BF16, oracle.BF16, 1), # bf16 in, four phases
+    (4, 4300000, 3, oracle.F32, oracle.F32, 1),          # slices not 16-byte aligned: the other kernel
+]
+
+
+@pytest.mark.parametrize("G,count,e0,in_dt,out_dt,knob", PHASED_CASES)
+def test_reduce_phased_parity(G, count, e0, in_dt, out_dt, knob):
+    g = synth.rng(0, 1900 + G, synth.KIND_GRAD, count % 1000)
+    total = e0 + count + 5
+    parts = []
+    for r in range(G):
+        x = g.standard_normal(total, dtype=np.float32) * np.float32(10.0 ** int(g.integers(-5, 2)))
+        parts.append(x if in_dt == oracle.F32 else synth.to_bf16_bits(x))
+    ies = 4 if in_dt == oracle.F32 else 2
+    oes = 4 if out_dt == oracle.F32 else 2
+    arena = Arena([total * ies] * G)
+    for r in range(G):
+        arena.fill(r, parts[r])
+    out = Arena([count * oes])
+    before = fcdp.fcdp_tuning_get("reduce_phased")
+    try:
+        fcdp.fcdp_tuning_set("reduce_phased", knob)
+        for scale in (None, float(np.float32(1.0 / G))):
+            want = oracle.reduce(parts, e0, count, out_dt, scale)
+            if scale is None:
+                fcdp.fcdp_reduce_grad_shard(arena.ptrs(), G, e0, count, in_dt, out_dt, out.ptr(0), None)
+            else:
+                fcdp.fcdp_reduce_grad_shard_scaled(arena.ptrs(), G, e0, count, in_dt, out_dt, scale,
+                                                   out.ptr(0), None)
+            torch.cuda.synchronize()
+            got = out.get(0, np.float32 if out_dt == oracle.F32 else np.uint16)
+            _cmp_reduce(got, want, out_dt)
+            out.check_guards()
+            if G > 8:
+                break                      # one pass is enough for the long ones
+    finally:
+        fcdp.fcdp_tuning_set("reduce_phased", before)
+    arena.check_guards()
+
+
+def test_reduce_phased_specials_in_place_and_both_kernels_agree():
+    """Through the phased kernel: Inf, NaN, signed zeros, denormals and
+    order-sensitive columns give the oracle's bits; rank 1 reduces in place
+    into its own slice; and the two kernels give the same bits."""
+    G, n = 6, 4194304 + 1028
+    specials = np.array([0x00000000, 0x80000000, 0x00000001, 0x80000001, 0x007FFFFF,
+                         0x00800000, 0x7F7FFFFF, 0xFF7FFFFF, 0x7F800000, 0xFF800000,
+                         0x7FC00000, 0x3F800000, 0xBF800000, 0x4B800000, 0x4B800001,
+                         0x33800000, 0x4CBEBC20, 0xCCBEBC20], dtype=np.uint32)
+    g = synth.rng(0, 78, synth.KIND_MISC)
+    parts = [specials[g.integers(0, specials.size, size=n)].view(np.float32).copy() for _ in range(G)]
+    parts[0][:2] = [2.0 ** 24, 1e8]
+    parts[1][:2] = [1.0, 1.0]
+    parts[2][:2] = [1.0, -1e8]
+    for r in range(3, G):
+        parts[r][:2] = 0.0
+    for r in range(G):
+        parts[r][2] = -0.0
+    before = fcdp.fcdp_tuning_get("reduce_phased")
+    try:
+        results = {}
+        for knob in (0, 1):
+            fcdp.fcdp_tuning_set("reduce_phased", knob)
+            for out_dt in (oracle.F32, oracle.BF16):
+                with np.errstate(all="ignore"):
+                    want = oracle.reduce(parts, 0, n, out_dt)
+                arena = Arena([n * 4] * G)
+                for r in range(G):
+                    arena.fill(r, parts[r])
+                out = Arena([n * (4 if out_dt == oracle.F32 else 2)])
+                fcdp.fcdp_reduce_grad_shard(arena.ptrs(), G, 0, n, fcdp.F32, out_dt, out.ptr(0), None)
+                torch.cuda.synchronize()
+                got = out.get(0, np.float32 if out_dt == oracle.F32 else np.uint16)
+                _cmp_reduce(got, want, out_dt)
+                results[(knob, out_dt)] = got.copy()
+                if out_dt == oracle.F32:
+                    assert got[0] == np.float32(2.0 ** 24) and got[1] == 0.0
+                    assert got.view(np.uint32)[2] == 0x80000000
+                    # in place: the sum lands in rank 1's own buffer
+                    fcdp.fcdp_reduce_grad_shard(arena.ptrs(), G, 0, n, fcdp.F32, fcdp.F32, arena.ptr(1), None)
+                    torch.cuda.synchronize()
+                    _cmp_reduce(arena.get(1, np.float32), want, out_dt)
+                    arena.check_guards()
+        for out_dt in (oracle.F32, oracle.BF16):
+            a, b = results[(0, out_dt)], results[(1, out_dt)]
+            if out_dt == oracle.F32:
+                a, b = a.view(np.uint32), b.view(np.uint32)
+                nan = np.isnan(results[(0, out_dt)])
+                assert np.array_equal(a[~nan], b[~nan])
+            else:
+                nan = ((a & 0x7F80) == 0x7F80) & ((a & 0x7F) != 0)   # payloads may differ
+                assert np.array_equal(a[~nan], b[~nan])
+    finally:
+        fcdp.fcdp_tuning_set("reduce_phased", before)
+
+
 PACK_CASES = [
     ("lora_like", [4096, 160, 160, 4096, 160, 160, 9000, 64], [0, 1, 1, 0, 1, 1, 0, 0], 8, 2),
     ("odd", [1001, 3, 777, 0, 12345, 1], [1, 0, 1, 1, 0, 1], 3, 2),
