@@ -2,14 +2,12 @@
 
 TEST INFRASTRUCTURE ONLY (see ``oracle/__init__.py``).
 
-The loop is replayed step by step in the order Alg. 1 gives: initialise every
-parameter dirty; forward over layers 1..L (a dirty parameter takes the
-inter-node gather and refreshes the host cache H, a clean one is loaded from
-H); backward over layers L..1 (always from H); one reduce-scatter of the
-trainable gradients; optimizer step; trainable parameters become dirty again.
-No data moves here: the replay records which source serves every parameter
-and how many elements cross the node boundary, which is what Sec. 6.2 and
-Sec. 6.3 count.
+A small state machine per parameter (validity flag, parameter version, cached
+version) with the three transitions the method defines -- forward use,
+backward use, optimizer step -- driven through the schedule of a training
+iteration (Alg. 1, Sec. 4.3, Sec. 4.5).  No data moves here: the replay
+records which source serves every parameter and how many elements cross the
+node boundary, which is what Sec. 6.2 and Sec. 6.3 count.
 """
 from __future__ import annotations
 
@@ -19,9 +17,51 @@ INTER = "inter"   # inter-node all-gather of the rank shards (cache miss)
 HOST = "host"     # host-cache load + intra-node gather (cache hit)
 
 
+class ParamCache:
+    """Cache state of one parameter: the validity flag Alg. 1 keeps for it, the
+    version the optimizer has produced and the version the host copy holds.
+    The three transitions are the only places the flag changes."""
+
+    def __init__(self, numel: int, trainable: bool):
+        self.numel, self.trainable = numel, trainable
+        self.dirty = True          # nothing is cached before the first forward pass
+        self.version = 0           # bumped by every optimizer step that touches it
+        self.cached_version = None
+
+    def forward(self) -> Tuple[str, int]:
+        """Source that serves the forward pass, and elements that cross the
+        node boundary for it.  A miss refreshes the host copy (Sec. 4.3,
+        Sec. 4.5: trainable parameters are invalid after every step, frozen
+        ones stay cached for the whole run)."""
+        if self.dirty:
+            self.cached_version = self.version
+            self.dirty = False
+            return INTER, self.numel
+        return HOST, 0
+
+    def backward(self) -> str:
+        """The backward pass never leaves the node: always the host copy."""
+        return HOST
+
+    def step(self) -> bool:
+        """Optimizer step: a trainable parameter changes and its cached copy
+        becomes invalid; returns whether that happened."""
+        if self.trainable:
+            self.version += 1
+            self.dirty = True
+        return self.trainable
+
+    def stale(self) -> bool:
+        return self.cached_version != self.version
+
+
 def replay(layers: Sequence[Sequence[Tuple[str, int, bool]]],
            iterations: int) -> Dict[str, object]:
     """layers[l] = [(param name, numel, trainable)], returns the trace.
+
+    Drives one ParamCache per parameter through the schedule of a training
+    iteration (forward over the layers in order, backward in reverse, one
+    reduce-scatter of the trainable gradients, optimizer step).
 
     trace["events"]: list of (iteration, phase, layer, name, what) with phase
     in {"fwd", "bwd", "rs", "upd"}; what in {INTER, HOST, "store", "dirty"}.
@@ -29,49 +69,37 @@ def replay(layers: Sequence[Sequence[Tuple[str, int, bool]]],
     cross the node boundary in that iteration (times (N-1)/N for the exact
     per-node share, which Sec. 6.2 approximates by 1).
     """
-    dirty: Dict[Tuple[int, str], bool] = {}
-    H: Dict[Tuple[int, str], int] = {}      # version of the cached copy
-    version: Dict[Tuple[int, str], int] = {}
-    for l, layer in enumerate(layers):
-        for name, _numel, _tr in layer:
-            dirty[(l, name)] = True
-            version[(l, name)] = 0
+    params = [[(name, ParamCache(numel, tr)) for name, numel, tr in layer] for layer in layers]
+    trainable_elems = sum(pc.numel for layer in params for _n, pc in layer if pc.trainable)
     events: List[tuple] = []
     vol: List[Dict[str, int]] = []
     stale_reads = 0
+    order = list(range(len(params)))
     for it in range(iterations):
         v = {"fwd": 0, "bwd": 0, "rs": 0}
-        for l, layer in enumerate(layers):
-            for name, numel, _tr in layer:
-                key = (l, name)
-                if dirty[key]:
-                    events.append((it, "fwd", l, name, INTER))
-                    v["fwd"] += numel
-                    H[key] = version[key]
-                    dirty[key] = False
-                    events.append((it, "fwd", l, name, "store"))
-                else:
-                    events.append((it, "fwd", l, name, HOST))
-                    if H[key] != version[key]:
+        for phase, sweep in (("fwd", order), ("bwd", order[::-1])):
+            for l in sweep:
+                for name, pc in params[l]:
+                    if phase == "fwd":
+                        src, crossed = pc.forward()
+                        v["fwd"] += crossed
+                    else:
+                        src = pc.backward()
+                    events.append((it, phase, l, name, src))
+                    if src == INTER:
+                        events.append((it, phase, l, name, "store"))
+                    elif pc.stale():
                         stale_reads += 1
-        for l in range(len(layers) - 1, -1, -1):
-            for name, numel, _tr in layers[l]:
-                key = (l, name)
-                events.append((it, "bwd", l, name, HOST))
-                if H[key] != version[key]:
-                    stale_reads += 1
-        wt = sum(numel for layer in layers for _n, numel, tr in layer if tr)
-        v["rs"] = wt
+        v["rs"] = trainable_elems                      # only grad W_t is reduced (Sec. 4.5, Sec. 6.3)
         events.append((it, "rs", -1, "grad_W_t", INTER))
-        for l, layer in enumerate(layers):
-            for name, _numel, tr in layer:
-                if tr:
-                    version[(l, name)] += 1     # optimizer step changes W_t
-                    dirty[(l, name)] = True
+        for l in order:
+            for name, pc in params[l]:
+                if pc.step():
                     events.append((it, "upd", l, name, "dirty"))
         vol.append(v)
+    dirty = {(l, name): pc.dirty for l in order for name, pc in params[l]}
     return {"events": events, "inter_elems": vol, "stale_reads": stale_reads,
-            "dirty": dict(dirty)}
+            "dirty": dirty}
 
 
 def replay_adaptive(layer_bytes: Sequence[int], utilisation, tau: float,

@@ -16,8 +16,7 @@
  * running sum; N = off[T]; Q = G*q (q = 64); N_pad = ceil(N/Q)*Q;
  * S = N_pad/G.  Flat index i lives in shard (i div S) at position (i mod S).
  * Each of the G data-parallel ranks owns one shard of S = W_l/G elements
- * (Sec. 2.1 "ZeRO-3 shards all three components"; Sec. 6.1 "each GPU stores
- * a shard of size W/G").
+ * (the sharding of Sec. 2.1; the per-GPU parameter memory of Sec. 6.1).
  *
  * Parity pins: every function here is pinned by tests that do not use it to
  * check itself (invariants, closed forms from Sec. 5.1 / Sec. 6.1, numpy and
