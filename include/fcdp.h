@@ -47,8 +47,12 @@
  *     thread-local text for the last failing call on the calling thread.
  *   - Zero-element tensors, N = 0 and N_t = 0 are legal no-ops.
  *   - Threads: a layout is immutable and may be shared.  Data calls may come
- *     from several threads, but calls that share a staging buffer, a cache
- *     state object or the timing pool must be serialised by the caller.
+ *     from several threads: the event ring, the staging-buffer table, the
+ *     list of copies in flight and the link counters of a device are guarded,
+ *     and a thread that has to wait for the oldest copy in flight waits
+ *     without holding that guard.  Calls that share a staging buffer, a cache
+ *     state object, the static staging array or the timing pool (i.e. any
+ *     data call while timing is enabled) must be serialised by the caller.
  */
 #ifndef FCDP_H
 #define FCDP_H
@@ -95,8 +99,8 @@ typedef enum {
 #define FCDP_MAX_G 64 /* most shards / gradient partials per call */
 
 /* ------------------------------------------------------------ offset table
- * Builds the layout of one layer (Sec. 2.1 "ZeRO-3 shards ... across all
- * GPUs"; Sec. 6.1 "each GPU stores a shard of size W/G").
+ * Builds the layout of one layer: every rank keeps an equal 1/G share of the
+ * flat parameter buffer (Sec. 2.1; the per-GPU parameter memory of Sec. 6.1).
  *   numel[t]      elements of tensor t (>= 0), t in [0, n_tensors)
  *   trainable[t]  1 = trainable (W_t), 0 = frozen (W_f); NULL = all trainable
  *                 (Sec. 4.5: parameters are classified once, at initialisation)
@@ -178,7 +182,13 @@ fcdp_status fcdp_layout_prepare(const fcdp_layout *layout);
  *   shard_ptrs   host array of G dev ptrs, S*elem_size bytes each
  *                (DEVICE_SHARDS only, else may be NULL)
  *   host_cache   host ptr to N_pad*elem_size bytes of pinned memory; read
- *                for HOST_*, written when store_cache is set; else may be NULL
+ *                for HOST_*, written when store_cache is set; else may be NULL.
+ *                Every host-link path checks it: memory HIP does not know as
+ *                pinned host memory (malloc, numpy, pageable) is refused with
+ *                FCDP_ENOTPINNED before anything is enqueued, because a copy
+ *                from or to pageable memory is not asynchronous and would
+ *                silently serialise the cache traffic with the kernels; the
+ *                zero-copy paths also need it mapped (fcdp_host_cache_alloc)
  *   staging      dev ptr to N_pad*elem_size bytes (HOST_DMA only)
  *   tensor_ptrs  host array of T dev ptrs, numel[t]*elem_size bytes each
  *                (entries of zero-element tensors are ignored)
@@ -360,6 +370,14 @@ fcdp_status fcdp_cache_state_backward_source(const fcdp_cache_state *state,
                                              fcdp_source host_mode,
                                              fcdp_source *src);
 fcdp_status fcdp_cache_state_optimizer_step(fcdp_cache_state *state);
+/* forward_source marks a class clean when it hands it out for storing,
+ * before the store is enqueued.  If that store (fcdp_materialize_layer with
+ * store_cache, or fcdp_cache_store) then fails, the host image was never
+ * written: call this to make the class dirty again, so that backward_source
+ * answers FCDP_ESTATE instead of serving it and the next forward pass takes
+ * the miss path.  Also ends the layer's device residency. */
+fcdp_status fcdp_cache_state_mark_dirty(fcdp_cache_state *state, int32_t layer,
+                                        int32_t klass);
 /* 1 dirty, 0 clean, -1 bad argument */
 int32_t fcdp_cache_state_is_dirty(const fcdp_cache_state *state, int32_t layer,
                                   int32_t klass);
@@ -383,9 +401,12 @@ fcdp_status fcdp_cache_state_place(fcdp_cache_state *state, int32_t layer,
                                    int32_t *keep);
 fcdp_status fcdp_cache_state_release(fcdp_cache_state *state, int32_t layer);
 
-/* Bytes this process has sent over the host link through the library on the
- * current device since the last reset: cache stores (device to host) and
- * cache fetches (host to device), DMA and zero-copy alike. */
+/* Bytes of layer images this process has moved over the host link through
+ * the library on the current device since the last reset: N_pad*elem_size per
+ * cache store (device to host) and per cache fetch (host to device), counted
+ * the same way for every mode (the zero-copy and per-tensor fetches leave the
+ * tail padding, fewer than G*pad_quantum elements, off the wire).  The
+ * counters are atomic; data calls from several threads may add to them. */
 fcdp_status fcdp_link_bytes(int32_t reset, int64_t *stored, int64_t *fetched);
 
 /* ------------------------------------------------------------------- misc */

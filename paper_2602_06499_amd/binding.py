@@ -50,6 +50,7 @@ EXPORTS = [
     "fcdp_cache_state_create", "fcdp_cache_state_destroy",
     "fcdp_cache_state_forward_source", "fcdp_cache_state_backward_source",
     "fcdp_cache_state_optimizer_step", "fcdp_cache_state_is_dirty",
+    "fcdp_cache_state_mark_dirty",
     "fcdp_cache_state_set_tau", "fcdp_cache_state_place",
     "fcdp_cache_state_release", "fcdp_link_bytes",
     "fcdp_status_string", "fcdp_last_error", "fcdp_tuning_set",
@@ -123,6 +124,7 @@ def load_library() -> ctypes.CDLL:
     lib.fcdp_cache_state_backward_source.argtypes = [vp, i32, i32, c.c_int, c.POINTER(c.c_int)]
     lib.fcdp_cache_state_optimizer_step.argtypes = [vp]
     lib.fcdp_cache_state_is_dirty.argtypes = [vp, i32, i32]
+    lib.fcdp_cache_state_mark_dirty.argtypes = [vp, i32, i32]
     lib.fcdp_cache_state_is_dirty.restype = i32
     lib.fcdp_status_string.argtypes = [c.c_int]
     lib.fcdp_status_string.restype = c.c_char_p
@@ -400,6 +402,9 @@ class CacheState:
 
     def release(self, layer: int) -> None:
         _check(load_library().fcdp_cache_state_release(self.handle, layer))
+
+    def mark_dirty(self, layer: int, klass: int) -> None:
+        _check(load_library().fcdp_cache_state_mark_dirty(self.handle, layer, klass))
 
     def is_dirty(self, layer: int, klass: int) -> int:
         return load_library().fcdp_cache_state_is_dirty(self.handle, layer, klass)

@@ -6,8 +6,10 @@
 #include <unistd.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstring>
+#include <deque>
 #include <mutex>
 #include <new>
 #include <string>
@@ -55,10 +57,12 @@ struct DeviceCtx {
     };
     StagingUse uses[8];
     uint64_t clock = 0;
-    // completion events of the host-link copies still in flight, oldest first
-    int64_t stored_bytes = 0, fetched_bytes = 0;
-    std::vector<hipEvent_t> copy_done;   // ring storage
-    size_t copy_head = 0, copy_count = 0;
+    // bytes of layer images sent over the host link (any thread may add)
+    std::atomic<int64_t> stored_bytes{0}, fetched_bytes{0};
+    // completion events of the host-link copies still in flight, oldest
+    // first, and events ready for reuse; both guarded by mu
+    std::deque<hipEvent_t> copies_in_flight;
+    std::vector<hipEvent_t> copy_events_free;
 };
 
 DeviceCtx g_ctx[fcdp::kMaxDevices];
@@ -108,22 +112,20 @@ fcdp_status current_ctx(DeviceCtx **out)
     return FCDP_OK;
 }
 
-// dst stream waits for everything enqueued so far on src stream
+// dst stream waits for everything enqueued so far on src stream.  Record and
+// wait happen under the lock (neither blocks), so two threads never hold the
+// same event of the ring between its record and its wait.
 fcdp_status order_after(DeviceCtx *ctx, hipStream_t src, hipStream_t dst)
 {
     if (src == dst) return FCDP_OK;
+    std::lock_guard<std::mutex> lk(ctx->mu);
     hipEvent_t ev;
-    {
-        std::lock_guard<std::mutex> lk(ctx->mu);
-        if (ctx->ring.size() < kRing) {
-            hipEvent_t e;
-            FCDP_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming), "hipEventCreate");
-            ctx->ring.push_back(e);
-            ev = e;
-        } else {
-            ev = ctx->ring[ctx->next];
-            ctx->next = (ctx->next + 1) % kRing;
-        }
+    if (ctx->ring.size() < kRing) {
+        FCDP_HIP(hipEventCreateWithFlags(&ev, hipEventDisableTiming), "hipEventCreate");
+        ctx->ring.push_back(ev);
+    } else {
+        ev = ctx->ring[ctx->next];
+        ctx->next = (ctx->next + 1) % kRing;
     }
     FCDP_HIP(hipEventRecord(ev, src), "hipEventRecord");
     FCDP_HIP(hipStreamWaitEvent(dst, ev, 0), "hipStreamWaitEvent");
@@ -132,47 +134,52 @@ fcdp_status order_after(DeviceCtx *ctx, hipStream_t src, hipStream_t dst)
 
 // Back-pressure on host-link copies: call before enqueueing one (may block on
 // the host until the oldest queued copy has finished), then copy_enqueued()
-// right after it.
+// right after it.  The wait happens outside the lock: the event waited for
+// has been taken off the list, so no other thread can record it meanwhile.
 fcdp_status copy_admit(DeviceCtx *ctx)
 {
     const int64_t cap = fcdp::tuning().max_copies_in_flight;
     if (cap <= 0) return FCDP_OK;
-    std::lock_guard<std::mutex> lk(ctx->mu);
-    if (ctx->copy_done.size() != static_cast<size_t>(cap)) {
-        // (re)size: drain what is tracked, then rebuild the ring
-        for (size_t i = 0; i < ctx->copy_count; ++i)
-            FCDP_HIP(hipEventSynchronize(ctx->copy_done[(ctx->copy_head + i) % ctx->copy_done.size()]), "hipEventSynchronize");
-        for (hipEvent_t e : ctx->copy_done) (void)hipEventDestroy(e);
-        ctx->copy_done.clear();
-        ctx->copy_head = ctx->copy_count = 0;
-        for (int64_t i = 0; i < cap; ++i) {
-            hipEvent_t e;
-            FCDP_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming), "hipEventCreate");
-            ctx->copy_done.push_back(e);
+    for (;;) {
+        hipEvent_t oldest = nullptr;
+        {
+            std::lock_guard<std::mutex> lk(ctx->mu);
+            // retire finished copies without blocking
+            while (!ctx->copies_in_flight.empty() && hipEventQuery(ctx->copies_in_flight.front()) == hipSuccess) {
+                ctx->copy_events_free.push_back(ctx->copies_in_flight.front());
+                ctx->copies_in_flight.pop_front();
+            }
+            (void)hipGetLastError(); // hipEventQuery reports "not ready" as an error code
+            if (static_cast<int64_t>(ctx->copies_in_flight.size()) < cap) return FCDP_OK;
+            oldest = ctx->copies_in_flight.front();
+            ctx->copies_in_flight.pop_front();
         }
+        hipError_t e = hipEventSynchronize(oldest);
+        {
+            std::lock_guard<std::mutex> lk(ctx->mu);
+            ctx->copy_events_free.push_back(oldest);
+        }
+        if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize");
     }
-    // retire finished copies without blocking, then block only if still full
-    while (ctx->copy_count > 0 && hipEventQuery(ctx->copy_done[ctx->copy_head]) == hipSuccess) {
-        ctx->copy_head = (ctx->copy_head + 1) % ctx->copy_done.size();
-        --ctx->copy_count;
-    }
-    (void)hipGetLastError(); // hipEventQuery reports "not ready" as an error code
-    if (ctx->copy_count == ctx->copy_done.size()) {
-        FCDP_HIP(hipEventSynchronize(ctx->copy_done[ctx->copy_head]), "hipEventSynchronize");
-        ctx->copy_head = (ctx->copy_head + 1) % ctx->copy_done.size();
-        --ctx->copy_count;
-    }
-    return FCDP_OK;
 }
 
 fcdp_status copy_enqueued(DeviceCtx *ctx, hipStream_t copy)
 {
     if (fcdp::tuning().max_copies_in_flight <= 0) return FCDP_OK;
     std::lock_guard<std::mutex> lk(ctx->mu);
-    if (ctx->copy_done.empty() || ctx->copy_count == ctx->copy_done.size()) return FCDP_OK;
-    hipEvent_t e = ctx->copy_done[(ctx->copy_head + ctx->copy_count) % ctx->copy_done.size()];
-    FCDP_HIP(hipEventRecord(e, copy), "hipEventRecord");
-    ++ctx->copy_count;
+    hipEvent_t e = nullptr;
+    if (!ctx->copy_events_free.empty()) {
+        e = ctx->copy_events_free.back();
+        ctx->copy_events_free.pop_back();
+    } else {
+        FCDP_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming), "hipEventCreate");
+    }
+    hipError_t err = hipEventRecord(e, copy);
+    if (err != hipSuccess) {
+        ctx->copy_events_free.push_back(e);
+        return hip_fail(err, "hipEventRecord");
+    }
+    ctx->copies_in_flight.push_back(e);
     return FCDP_OK;
 }
 
@@ -310,6 +317,26 @@ fcdp_status mapped_alias(void *host, const char *fn, void **alias)
     if (attr.type != hipMemoryTypeHost || !attr.devicePointer)
         return fail(FCDP_ENOTPINNED, std::string(fn) + ": host_cache is not mapped pinned host memory");
     *alias = attr.devicePointer;
+    return FCDP_OK;
+}
+
+// FCDP_OK if [host, host + bytes) is pinned host memory known to HIP (mapped
+// or not), else FCDP_ENOTPINNED.  With pageable memory hipMemcpyAsync stops
+// being asynchronous, and the overlap of the cache traffic with the kernels,
+// which is what the host cache is for, is silently gone.
+fcdp_status require_pinned(const void *host, size_t bytes, const char *fn)
+{
+    const char *ends[2] = {static_cast<const char *>(host),
+                           static_cast<const char *>(host) + (bytes ? bytes - 1 : 0)};
+    for (const char *p : ends) {
+        hipPointerAttribute_t attr;
+        std::memset(&attr, 0, sizeof attr);
+        hipError_t e = hipPointerGetAttributes(&attr, p);
+        if (e != hipSuccess) (void)hipGetLastError(); // clear the error an unknown pointer leaves
+        if (e != hipSuccess || attr.type != hipMemoryTypeHost)
+            return fail(FCDP_ENOTPINNED, std::string(fn) + ": host_cache is not pinned host memory "
+                                                           "(allocate it with fcdp_host_cache_alloc or hipHostMalloc)");
+    }
     return FCDP_OK;
 }
 
@@ -507,12 +534,17 @@ try {
         if (src == FCDP_SRC_HOST_DMA) {
             if (!staging) return fail(FCDP_EINVAL, std::string(fn) + ": FCDP_SRC_HOST_DMA needs a staging buffer");
             if (!aligned16(staging)) return fail(FCDP_EALIGN, std::string(fn) + ": staging is not 16-byte aligned");
-        } else if (src == FCDP_SRC_HOST_ZEROCOPY && flat_bytes) {
+        }
+        if (src == FCDP_SRC_HOST_ZEROCOPY && flat_bytes) {
             if ((st = mapped_alias(host_cache, fn, &zc_alias)) != FCDP_OK) return st;
+        } else if (flat_bytes && (st = require_pinned(host_cache, flat_bytes, fn)) != FCDP_OK) {
+            return st;
         }
     }
     if (store_cache && !aligned16(host_cache))
         return fail(FCDP_EALIGN, std::string(fn) + ": host_cache is not 16-byte aligned");
+    if (store_cache == FCDP_STORE_DMA && flat_bytes && (st = require_pinned(host_cache, flat_bytes, fn)) != FCDP_OK)
+        return st;
     void *store_alias = nullptr;
     if (store_cache == FCDP_STORE_ZEROCOPY && flat_bytes) {
         if ((st = mapped_alias(host_cache, fn, &store_alias)) != FCDP_OK) return st;
@@ -556,8 +588,11 @@ try {
                           reinterpret_cast<const void *const *>(tensor_ptrs), tune.copy_nt != 0,
                           tune.copy_wg_per_cu, compute, "launch unflatten", FCDP_KERNEL_UNFLATTEN);
         if (st != FCDP_OK) return st;
-        FCDP_HIP(hipEventRecord(use->done, compute), "hipEventRecord(staging)");
-        use->staging = staging;
+        {
+            std::lock_guard<std::mutex> lk(ctx->mu);
+            FCDP_HIP(hipEventRecord(use->done, compute), "hipEventRecord(staging)");
+            use->staging = staging;
+        }
         ctx->fetched_bytes += static_cast<int64_t>(flat_bytes);
         return FCDP_OK;
     }
@@ -572,13 +607,13 @@ try {
                                     hipMemcpyHostToDevice, copy), "hipMemcpyAsync(H2D, per tensor)");
             if ((st = copy_enqueued(ctx, copy)) != FCDP_OK) return st;
         }
-        ctx->fetched_bytes += static_cast<int64_t>(L->N) * L->esz;
+        ctx->fetched_bytes += static_cast<int64_t>(flat_bytes);
         return order_after(ctx, copy, compute);
     }
     // zero-copy: the kernel's loads cross the host link
     if ((st = order_after(ctx, copy, compute)) != FCDP_OK) return st;
     for (int32_t r = 0; r < L->G; ++r) small[r] = static_cast<const char *>(zc_alias) + r * shard_bytes;
-    ctx->fetched_bytes += static_cast<int64_t>(L->N) * L->esz;
+    ctx->fetched_bytes += static_cast<int64_t>(flat_bytes);
     return run_windowed(L->unflatten, tabs->unflatten, fcdp::TensorSide::Dst, L->T, small, L->G,
                         reinterpret_cast<const void *const *>(tensor_ptrs), false, 0, compute,
                         "launch zero-copy unflatten", FCDP_KERNEL_UNFLATTEN_ZEROCOPY, tune.link_max_wgs,
@@ -604,6 +639,7 @@ try {
                                     " bytes) exceeds FCDP_STATIC_STAGING_BYTES (" +
                                     std::to_string(static_cast<size_t>(FCDP_STATIC_STAGING_BYTES)) + ")");
     if (L->N == 0) return FCDP_OK;
+    if ((st = require_pinned(host_cache, flat_bytes, fn)) != FCDP_OK) return st;
     int dev = 0;
     FCDP_HIP(hipGetDevice(&dev), "hipGetDevice");
     if (dev < 0 || dev >= fcdp::kMaxDevices)
@@ -673,6 +709,9 @@ try {
     if (L->N_pad == 0) return FCDP_OK;
     void *alias = nullptr;
     if (store_mode == FCDP_STORE_ZEROCOPY && (st = mapped_alias(host_cache, fn, &alias)) != FCDP_OK) return st;
+    if (store_mode == FCDP_STORE_DMA &&
+        (st = require_pinned(host_cache, static_cast<size_t>(L->N_pad) * L->esz, fn)) != FCDP_OK)
+        return st;
     DeviceCtx *ctx = nullptr;
     if ((st = current_ctx(&ctx)) != FCDP_OK) return st;
     return enqueue_store(L, ctx, shard_ptrs, host_cache, alias, store_mode,
@@ -686,9 +725,10 @@ try {
     DeviceCtx *ctx = nullptr;
     fcdp_status st = current_ctx(&ctx);
     if (st != FCDP_OK) return st;
-    if (stored) *stored = ctx->stored_bytes;
-    if (fetched) *fetched = ctx->fetched_bytes;
-    if (reset) ctx->stored_bytes = ctx->fetched_bytes = 0;
+    if (stored) *stored = reset ? ctx->stored_bytes.exchange(0) : ctx->stored_bytes.load();
+    if (fetched) *fetched = reset ? ctx->fetched_bytes.exchange(0) : ctx->fetched_bytes.load();
+    if (reset && !stored) ctx->stored_bytes = 0;
+    if (reset && !fetched) ctx->fetched_bytes = 0;
     return FCDP_OK;
 } catch (...) {
     return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_link_bytes: out of host memory");
@@ -993,6 +1033,19 @@ try {
     return FCDP_OK;
 } catch (...) {
     return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_cache_state_optimizer_step: out of host memory");
+}
+
+fcdp_status fcdp_cache_state_mark_dirty(fcdp_cache_state *s, int32_t layer, int32_t klass)
+try {
+    const char *fn = "fcdp_cache_state_mark_dirty";
+    if (!s) return fail(FCDP_EINVAL, std::string(fn) + ": NULL state");
+    if (layer < 0 || layer >= s->L || klass < 0 || klass > 1) return fail(FCDP_EINVAL, std::string(fn) + ": layer or class out of range");
+    s->dirty[static_cast<size_t>(layer) * 2 + klass] = 1;
+    s->pending[static_cast<size_t>(layer) * 2 + klass] = 0;
+    s->resident[layer] = 0;
+    return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_cache_state_mark_dirty: out of host memory");
 }
 
 fcdp_status fcdp_cache_state_set_tau(fcdp_cache_state *s, double tau)

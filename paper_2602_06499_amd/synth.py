@@ -49,15 +49,6 @@ class LayerConfig:
     def N(self) -> int:
         return int(sum(self.numel))
 
-    @property
-    def N_pad(self) -> int:
-        Q = self.G * self.pad_quantum
-        return ((self.N + Q - 1) // Q) * Q
-
-    @property
-    def S(self) -> int:
-        return self.N_pad // self.G
-
 
 def _gpt2_layer(hidden: int, ffn: int):
     names = ("ln_1.weight", "ln_1.bias", "attn.c_attn.weight",
@@ -118,11 +109,12 @@ def _mk_llama(name, cid, hidden, ffn, qh, kvh, G, layers, lora_rank=0,
 CONFIGS: Dict[str, LayerConfig] = {
     # GPT-2-small layer: hidden 768, FFN 3072, all four linears with bias.
     "gpt2_small_g4": _mk_gpt2("gpt2_small_g4", 1, 768, 3072, 4, 1),
-    # Llama-2-7B-shaped stack: the workload the headline metric is quoted on.
+    # Llama-2-7B-shaped stack, 32 layers.
     "llama7b_g8": _mk_llama("llama7b_g8", 2, 4096, 11008, 32, 32, 8, 32),
     # PEFT on the 7B shape: LoRA rank 16 on q_proj and v_proj.
     "llama7b_lora_g8": _mk_llama("llama7b_lora_g8", 3, 4096, 11008, 32, 32,
                                  8, 32, 16, ("q_proj", "v_proj")),
+    # 13B shape: 40 layers, every matrix straddles shard boundaries at G = 16.
     "llama13b_g16": _mk_llama("llama13b_g16", 4, 5120, 13824, 40, 40, 16, 40),
     # 70B shape with grouped-query attention: 64 query heads, 8 KV heads.
     "llama70b_g32": _mk_llama("llama70b_g32", 5, 8192, 28672, 64, 8, 32, 80),

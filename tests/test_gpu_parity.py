@@ -535,6 +535,62 @@ def test_tuning_variants_same_bytes():
             fcdp.fcdp_tuning_set(k, v)
 
 
+def test_every_host_link_path_rejects_pageable_memory():
+    """Sec. 4.4 wants the cache in pinned buffers: a numpy array (pageable)
+    as host_cache is FCDP_ENOTPINNED on every path that crosses the host
+    link, before anything is enqueued; pinned memory that is not from
+    fcdp_host_cache_alloc (torch's pin_memory) is accepted by the DMA paths
+    and gives the oracle's bytes."""
+    sizes, G = [5000, 3, 70001], 4
+    tensors = _rand_tensors(9, sizes, np.uint16)
+    flat = oracle.flatten(tensors, G)
+    shards = oracle.split(flat, G)
+    L = fcdp.fcdp_layout_build(sizes, None, G, 2)
+    L.prepare()
+    Np = L.padded_numel
+    sh = Arena([L.shard_numel * 2] * G)
+    for r in range(G):
+        sh.fill(r, shards[r])
+    out = Arena([k * 2 for k in sizes])
+    staging = Arena([Np * 2])
+    pageable = np.zeros(Np, dtype=np.uint16)
+    pageable[:] = flat
+    hp = pageable.ctypes.data
+    assert hp % 16 == 0
+    sentinel_before = out.buf.clone()
+    calls = {
+        "host_dma": lambda h: fcdp.fcdp_materialize_layer(L, fcdp.SRC_HOST_DMA, None, h, staging.ptr(0), out.ptrs()),
+        "host_scatter_dma": lambda h: fcdp.fcdp_materialize_layer(L, fcdp.SRC_HOST_SCATTER_DMA, None, h, None, out.ptrs()),
+        "host_zerocopy": lambda h: fcdp.fcdp_materialize_layer(L, fcdp.SRC_HOST_ZEROCOPY, None, h, None, out.ptrs()),
+        "static": lambda h: fcdp.fcdp_materialize_layer_static(L, h, out.ptrs()),
+        "store_dma": lambda h: fcdp.fcdp_materialize_layer(L, fcdp.SRC_DEVICE_SHARDS, sh.ptrs(), h, None, out.ptrs(),
+                                                           fcdp.STORE_DMA),
+        "store_zerocopy": lambda h: fcdp.fcdp_materialize_layer(L, fcdp.SRC_DEVICE_SHARDS, sh.ptrs(), h, None,
+                                                                out.ptrs(), fcdp.STORE_ZEROCOPY),
+        "cache_store_dma": lambda h: fcdp.fcdp_cache_store(L, sh.ptrs(), h, fcdp.STORE_DMA),
+        "cache_store_zerocopy": lambda h: fcdp.fcdp_cache_store(L, sh.ptrs(), h, fcdp.STORE_ZEROCOPY),
+    }
+    for name, call in calls.items():
+        with pytest.raises(fcdp.FcdpError) as e:
+            call(hp)
+        assert e.value.name == "FCDP_ENOTPINNED", name
+    torch.cuda.synchronize()
+    assert torch.equal(out.buf, sentinel_before), "a refused call wrote to the tensors"
+    # pinned memory from another allocator: fine for the DMA paths
+    pinned = torch.empty(Np, dtype=torch.int16).pin_memory()
+    fcdp.fcdp_materialize_layer(L, fcdp.SRC_DEVICE_SHARDS, sh.ptrs(), pinned.data_ptr(), None, out.ptrs(),
+                                fcdp.STORE_DMA)
+    torch.cuda.synchronize()
+    assert np.array_equal(pinned.numpy().view(np.uint16), flat)
+    for name in ("host_dma", "host_scatter_dma", "static"):
+        out.buf.fill_(0xC3)
+        calls[name](pinned.data_ptr())
+        torch.cuda.synchronize()
+        for t in range(len(sizes)):
+            assert np.array_equal(out.get(t, np.uint16), tensors[t]), name
+        out.check_guards()
+
+
 def test_zero_copy_rejects_unpinned_memory():
     sizes, G = [1024], 2
     L = fcdp.fcdp_layout_build(sizes, None, G, 2)
