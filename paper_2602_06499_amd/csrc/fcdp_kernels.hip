@@ -20,6 +20,7 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 
+#include <atomic>
 #include <cstdint>
 
 #include "fcdp_internal.h"
@@ -683,7 +684,7 @@ __global__ void __launch_bounds__(256) reduce_runs(const ReduceRunArgs a)
     }
 }
 
-int g_cu_count[kMaxDevices] = {0};
+std::atomic<int> g_cu_count[kMaxDevices]; // 0 = not asked yet; any thread may fill it in
 
 // Launches `kernel`; with timing events the dispatch itself carries them.
 template <typename K, typename A>
@@ -778,13 +779,13 @@ int device_cu_count()
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 256;
     if (dev < 0 || dev >= kMaxDevices) return 256;
-    if (g_cu_count[dev] == 0) {
-        int n = 0;
+    int n = g_cu_count[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
             n = 256;
-        g_cu_count[dev] = n;
+        g_cu_count[dev].store(n, std::memory_order_relaxed);
     }
-    return g_cu_count[dev];
+    return n;
 }
 
 int launch_copy(const CopyLaunch &c, void *stream)

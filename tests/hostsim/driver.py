@@ -224,6 +224,22 @@ def main():
         print("peft", name, flush=True)
         check_peft(name, sizes, tr, G, esz)
         n += 1
+    # the numa_node argument of the host cache allocation: every accepted value gives a
+    # usable buffer (the policy is best effort), the out-of-range one is an argument error
+    for node in (-1, 0, 1, 63, 1023):
+        H = fcdp.fcdp_host_cache_alloc(4096, numa_node=node)
+        note = fcdp.fcdp_last_error()
+        assert note == "" or "NUMA policy refused" in note or "no NUMA policy call" in note, note
+        H.numpy(np.uint8)[:] = 7
+        H.free()
+        n += 1
+    for bad in (1024, 1 << 20):
+        try:
+            fcdp.fcdp_host_cache_alloc(4096, numa_node=bad)
+        except fcdp.FcdpError as e:
+            assert e.name == "FCDP_EINVAL", e
+        else:
+            raise AssertionError("numa_node %d was accepted" % bad)
     print("hostsim ok: %d cases" % n, flush=True)
 
 

@@ -170,3 +170,99 @@ def test_adaptive_gpu_caching(tau):
         state.optimizer_step()
     for H in caches:
         H.free()
+
+
+@pytest.mark.parametrize("host_mode", [fcdp.SRC_HOST_DMA, fcdp.SRC_HOST_ZEROCOPY])
+def test_peft_loop_at_full_layer_size(host_mode):
+    """The PEFT loop of Alg. 1 on full-size layers (llama7b_lora_g8: 405 MB of
+    bf16 parameters, LoRA r16 on q and v, G = 8), three iterations over two
+    layers: a miss with a cache store in the first iteration; from the second
+    on the frozen class hits, the trainable class is refreshed by unpacking
+    the gathered packed values into the mapped host cache, and the layer is
+    materialized from there; every backward pass hits; the trainable gradient
+    shard comes from the fused pack + reduce with the mean's scale 1/G.  A
+    stand-in optimizer rewrites the LoRA tensors after every step.  Every
+    materialization, the cached image and every gradient shard are compared
+    with the oracle."""
+    cfg = synth.CONFIGS["llama7b_lora_g8"]
+    sizes, tr, G = list(cfg.numel), list(cfg.trainable), cfg.G
+    nl, iters = 2, 3
+    dev = torch.device("cuda:0")
+    L = fcdp.fcdp_layout_build(sizes, tr, G, 2)
+    L.prepare()
+    Np, S, pk = L.padded_numel, L.shard_numel, L.packed_numel
+    Sp = pk // G
+    params = [synth.layer_params_bf16(cfg, l, lora_b="zero") for l in range(nl)]
+    caches = [fcdp.fcdp_host_cache_alloc(Np * 2) for _ in range(nl)]
+    for H in caches:
+        H.numpy(np.uint16, Np)[:] = 0xDEAD
+    state = fcdp.CacheState(nl)
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    staging = [torch.zeros(Np, dtype=torch.int16, device=dev) for _ in range(2)]
+    outs = [torch.zeros(max(k, 1), dtype=torch.int16, device=dev) for k in sizes]
+    # G flat fp32 gradients of one layer, drawn on the device once; the optimizer
+    # stand-in below also rewrites their trainable ranges so every step sums new values
+    gen = synth.torch_device_generator(dev, cfg.config_id, 0, synth.KIND_GRAD)
+    d_grads = [torch.empty(Np, dtype=torch.float32, device=dev).normal_(0.0, 1e-3, generator=gen) for _ in range(G)]
+    h_grads = [d.cpu().numpy() for d in d_grads]
+    d_shard = torch.zeros(Sp, dtype=torch.float32, device=dev)
+    off = L.offsets
+    g = synth.rng(cfg.config_id, 99, synth.KIND_MISC)
+    scale = float(np.float32(1.0 / G))
+    kinds = []
+
+    def check(l, what):
+        torch.cuda.synchronize()
+        want = oracle.materialize_from_flat(oracle.flatten(params[l], G), sizes)
+        for t, k in enumerate(sizes):
+            assert np.array_equal(outs[t][:k].cpu().numpy().view(np.uint16), want[t]), (what, l, t)
+        for o in outs:
+            o.zero_()
+        torch.cuda.synchronize()
+
+    for it in range(iters):
+        for l in range(nl):                                       # ---- forward
+            flat = oracle.flatten(params[l], G)
+            dec = {c: state.forward_source(l, c, host_mode) for c in (0, 1)}
+            if all(src == fcdp.SRC_DEVICE_SHARDS for src, _ in dec.values()):
+                gathered = to_dev(flat)
+                ptrs = [gathered.data_ptr() + r * S * 2 for r in range(G)]
+                torch.cuda.synchronize()
+                fcdp.fcdp_materialize_layer(L, fcdp.SRC_DEVICE_SHARDS, ptrs, caches[l], None, outs,
+                                            fcdp.STORE_DMA, compute, copy)
+                kinds.append("miss")
+            else:
+                assert dec[0] == (host_mode, False) and dec[1] == (fcdp.SRC_DEVICE_SHARDS, True)
+                packed = to_dev(oracle.pack(flat, sizes, tr, G))     # what the gather of W_t delivers
+                torch.cuda.synchronize()
+                fcdp.fcdp_unpack_trainable(L, packed, caches[l].dev, copy)
+                fcdp.fcdp_materialize_layer(L, host_mode, None, caches[l], staging[l % 2], outs,
+                                            fcdp.STORE_NONE, compute, copy)
+                kinds.append("refresh")
+            check(l, "forward it%d" % it)
+            assert np.array_equal(caches[l].numpy(np.uint16, Np), flat), "host cache is not the current layer"
+        for l in range(nl - 1, -1, -1):                           # ---- backward
+            for c in (0, 1):
+                assert state.backward_source(l, c, host_mode) == host_mode
+            fcdp.fcdp_materialize_layer(L, host_mode, None, caches[l], staging[l % 2], outs,
+                                        fcdp.STORE_NONE, compute, copy)
+            check(l, "backward it%d" % it)
+            rank = (it * nl + l) % G
+            fcdp.fcdp_reduce_trainable_shard_scaled(L, d_grads, rank, fcdp.F32, fcdp.F32, scale, d_shard, compute)
+            torch.cuda.synchronize()
+            want = oracle.reduce_trainable(h_grads, sizes, tr, G, rank, oracle.F32, scale=scale)
+            assert np.array_equal(d_shard.cpu().numpy().view(np.uint32), want.view(np.uint32)), (it, l, rank)
+        for l in range(nl):                                       # ---- optimizer step
+            for t, k in enumerate(sizes):
+                if tr[t]:
+                    params[l][t] = g.integers(0, 65536, size=k, dtype=np.uint16)
+        for t, k in enumerate(sizes):
+            if tr[t]:
+                for r in range(G):
+                    x = g.standard_normal(k, dtype=np.float32) * np.float32(1e-3)
+                    h_grads[r][off[t]:off[t] + k] = x
+                    d_grads[r][off[t]:off[t] + k] = torch.from_numpy(x).to(dev)
+        state.optimizer_step()
+    assert kinds == ["miss"] * nl + ["refresh"] * (nl * (iters - 1))
+    for H in caches:
+        H.free()

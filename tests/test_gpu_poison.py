@@ -60,20 +60,36 @@ def test_poison_is_written_first(poison):
     out = Arena([k * 2 for k in sizes])
     staging = Arena([Np * 2])
     compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
-    snap = torch.empty_like(out.buf)
+    # Streams share a few hardware queues, so a snapshot stream may sit behind the
+    # held-back `copy` or behind `compute`'s wait for it, depending on how many streams
+    # the process made before; eight side streams cover every queue, and the snapshots
+    # that do run meanwhile must show the pattern
+    sides = [torch.cuda.Stream() for _ in range(8)]
+    snaps = [torch.empty_like(out.buf) for _ in sides]
     torch.cuda.synchronize()
     with torch.cuda.stream(copy):
         torch.cuda._sleep(order.SPIN)
     fcdp.fcdp_materialize_layer(L, fcdp.SRC_HOST_DMA, None, H, staging.ptr(0), out.ptrs(),
                                 fcdp.STORE_NONE, compute, copy)
     time.sleep(0.003)             # the fill runs at once on the idle stream (microseconds)
-    side = torch.cuda.Stream()
-    with torch.cuda.stream(side):
-        snap.copy_(out.buf)       # the scatter is still blocked behind `copy`
+    for side, snap in zip(sides, snaps):
+        with torch.cuda.stream(side):
+            snap.copy_(out.buf)   # the scatter is still blocked behind `copy`
     torch.cuda.synchronize()
-    h = snap.cpu().numpy()
-    for o, nb in out.ranges:
-        assert np.all(h[o:o + nb].view(np.uint16) == 0x7FC1), "tensor was not poisoned ahead of the fetch"
+    poisoned = 0
+    for snap in snaps:
+        h = snap.cpu().numpy()
+        states = []
+        for (o, nb), want in zip(out.ranges, tensors):
+            got = h[o:o + nb].view(np.uint16)
+            if np.all(got == 0x7FC1):
+                states.append("poison")
+            else:
+                # a snapshot that ran late sees the finished layer, never stale bytes
+                assert np.array_equal(got, want), "tensor holds neither the pattern nor the layer"
+                states.append("layer")
+        poisoned += all(st == "poison" for st in states)
+    assert poisoned >= 1, "no snapshot saw the tensors poisoned ahead of the fetch"
     for t, k in enumerate(sizes):
         assert np.array_equal(out.get(t, np.uint16), tensors[t])
     out.check_guards()

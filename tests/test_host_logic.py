@@ -354,6 +354,35 @@ def test_cache_state_errors():
         fcdp.CacheState(0)
 
 
+def test_failed_store_can_be_rolled_back():
+    """forward_source marks a class clean before the caller's store runs; if
+    the store fails the caller marks it dirty again: backward_source refuses
+    to serve an image that was never written, and the next forward pass is a
+    miss again."""
+    st = fcdp.CacheState(3)
+    assert st.forward_source(1, 0, fcdp.SRC_HOST_DMA) == (fcdp.SRC_DEVICE_SHARDS, True)
+    assert st.is_dirty(1, 0) == 0
+    assert st.backward_source(1, 0, fcdp.SRC_HOST_DMA) == fcdp.SRC_HOST_DMA   # would serve it
+    st.mark_dirty(1, 0)                                                      # ... the store failed
+    assert st.is_dirty(1, 0) == 1
+    with pytest.raises(fcdp.FcdpError) as e:
+        st.backward_source(1, 0, fcdp.SRC_HOST_DMA)
+    assert e.value.name == "FCDP_ESTATE"
+    assert st.forward_source(1, 0, fcdp.SRC_HOST_DMA) == (fcdp.SRC_DEVICE_SHARDS, True)
+    # a resident layer loses its residency too
+    st.set_tau(1.0)
+    st.forward_source(2, 1, fcdp.SRC_HOST_DMA)
+    assert st.place(2, 1, 100) is True
+    assert st.backward_source(2, 1, fcdp.SRC_HOST_DMA) == fcdp.SRC_DEVICE_RESIDENT
+    st.mark_dirty(2, 1)
+    with pytest.raises(fcdp.FcdpError):
+        st.backward_source(2, 1, fcdp.SRC_HOST_DMA)
+    for bad in ((3, 0), (-1, 0), (0, 2)):
+        with pytest.raises(fcdp.FcdpError) as e:
+            st.mark_dirty(*bad)
+        assert e.value.name == "FCDP_EINVAL"
+
+
 def test_no_gpu_means_loud_failure():
     """Without a device a valid data call returns FCDP_EHIP; it never falls
     back to a CPU path."""
