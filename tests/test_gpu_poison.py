@@ -51,6 +51,7 @@ def test_poison_is_written_first(poison):
     pattern everywhere; afterwards the tensors hold the layer."""
     sizes, G = [70000, 5, 65536, 9], 4
     L = fcdp.fcdp_layout_build(sizes, None, G, 2)
+    L.prepare()       # else the call below uploads the tables, a synchronous copy that may queue behind the held-back stream
     Np = L.padded_numel
     tensors = [synth.rng(0, 3, synth.KIND_MISC, t).integers(0, 65536, size=k, dtype=np.uint16)
                for t, k in enumerate(sizes)]
