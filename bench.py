@@ -48,9 +48,9 @@ LINK_PEAK_GBPS = 63.0           # PCIe Gen5 x16 per direction, 128b/130b
 TRAFFIC_SOURCE = "profiles/unflatten_reduce_hbm_traffic.md"
 MEASURED_TRAFFIC = {
     # config: (unflatten, reduce fp32 out, reduce bf16 out) in bytes per launch
-    "llama7b_g8": (822.2e6, 910.7e6, 860.2e6),
-    "llama13b_g16": (1288.7e6, 1348.1e6, 1308.5e6),
-    "llama70b_g32": (3476.0e6, 3529.5e6, 3475.9e6),
+    "llama7b_g8": (822.2e6, 911.3e6, 860.2e6),
+    "llama13b_g16": (1288.7e6, 1348.7e6, 1309.2e6),
+    "llama70b_g32": (3476.1e6, 3530.1e6, 3476.9e6),
 }
 
 
@@ -87,6 +87,10 @@ def parse():
     ap.add_argument("--cpu-threads", type=int, default=4,
                     help="threads of the all-threads oracle leg (one layer each)")
     ap.add_argument("--probe-gib", type=int, default=2, help="size of the host-link probe copy")
+    ap.add_argument("--reduce-study", action="store_true",
+                    help="instead of the benchmark: the gradient-shard reduce at the 7B / 13B / 70B shard sizes "
+                         "(G = 8, 16, 32) with both kernels, next to the G:1 calibration stream and a read-only "
+                         "pass; prints one JSON line")
     return ap.parse_args()
 
 
@@ -219,7 +223,8 @@ class Stack:
                                             self.store_mode, compute, copy)
                 st.place(l, self.total_mem, self.total_mem)
         if record is not None:
-            e1 = ev(enable_timing=True); e1.record(copy)
+            # the forward sweep ends when its last store does (no stores at tau = 1: on `compute`)
+            e1 = ev(enable_timing=True); e1.record(copy if self.tau < 1.0 else compute)
         for l in range(self.L - 1, -1, -1):
             src = st.backward_source(l, 1, self.host_mode)
             fcdp.fcdp_materialize_layer(lay, src, None, self.slot(l), self.staging[l % 2],
@@ -304,6 +309,58 @@ class Stack:
         # allocator keeps the blocks and the next leg reuses them
 
 
+def reduce_study(fcdp, synth, torch):
+    """Kernel-only times (dispatch events) of the reduce on cold, rotating
+    inputs, nothing else running: calibration stream, one tile per workgroup,
+    phased; fp32 partials, fp32 and bf16 shard."""
+    dev = torch.device("cuda:0")
+    st = torch.cuda.Stream()
+    rows = []
+    before = fcdp.fcdp_tuning_get("reduce_phased")
+    for cname in ("llama7b_g8", "llama13b_g16", "llama70b_g32"):
+        cfg = synth.CONFIGS[cname]
+        G = cfg.G
+        S = fcdp.fcdp_layout_build(cfg.numel, cfg.trainable, G, 2).shard_numel
+        Sc = S // 1024 * 1024                    # the calibration stream takes whole tiles
+        NB = 3
+        ps = [torch.empty(G, S, dtype=torch.float32, device=dev).normal_(0, 1e-3) for _ in range(NB)]
+        ptrs = [fcdp.pointer_array([p.data_ptr() + r * S * 4 for r in range(G)]) for p in ps]
+        outs = [torch.empty(S, dtype=torch.float32, device=dev) for _ in range(NB)]
+        torch.cuda.synchronize()
+
+        def timed(kind, fn, reps=30):
+            for i in range(3):
+                fn(i)
+            torch.cuda.synchronize()
+            fcdp.fcdp_timing_enable(reps + 4)
+            for i in range(reps):
+                fn(i)
+            torch.cuda.synchronize()
+            n, ms = fcdp.fcdp_timing_collect(kind)
+            fcdp.fcdp_timing_enable(0)
+            return ms / n
+
+        for odt, oname, osz in ((fcdp.F32, "fp32", 4), (fcdp.BF16, "bf16", 2)):
+            row = {"config": cname, "G": G, "S": S, "out": oname}
+            cal = timed(fcdp.KERNEL_PROBE_STREAM, lambda i: fcdp.fcdp_probe_reduce_stream(
+                outs[i % NB], ps[i % NB], G, Sc, odt, st))
+            row["calibration_stream_us"] = round(cal * 1e3, 1)
+            row["calibration_stream_gbps"] = round((G * Sc * 4 + Sc * osz) / (cal * 1e-3) / 1e9, 1)
+            for knob, name in ((0, "tiles"), (1, "phased")):
+                fcdp.fcdp_tuning_set("reduce_phased", knob)
+                ms = timed(fcdp.KERNEL_REDUCE, lambda i: fcdp.fcdp_reduce_grad_shard(
+                    ptrs[i % NB], G, 0, S, fcdp.F32, odt, outs[i % NB], st))
+                row[name + "_us"] = round(ms * 1e3, 1)
+                row[name + "_gbps"] = round((G * S * 4 + S * osz) / (ms * 1e-3) / 1e9, 1)
+                row[name + "_frac"] = round((G * S * 4 + S * osz) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
+                row[name + "_vs_calibration"] = round(row[name + "_gbps"] / row["calibration_stream_gbps"], 4)
+            fcdp.fcdp_tuning_set("reduce_phased", before)
+            rows.append(row)
+        del ps, outs
+    print(json.dumps({"study": "gradient-shard reduce against the G:1 calibration stream", "peak_gbps": HBM_PEAK_GBPS,
+                      "rows": rows}), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -318,6 +375,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    if args.reduce_study:
+        reduce_study(fcdp, synth, torch)
+        return
     host = host_info()
     if args.copies_in_flight >= 0:
         fcdp.fcdp_tuning_set("max_copies_in_flight", args.copies_in_flight)

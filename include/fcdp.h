@@ -469,7 +469,8 @@ typedef enum {
     FCDP_KERNEL_UNPACK = 5,
     FCDP_KERNEL_STORE_ZEROCOPY = 6,
     FCDP_KERNEL_PROBE_COPY = 7,
-    FCDP_KERNEL_REDUCE_TRAINABLE = 8
+    FCDP_KERNEL_REDUCE_TRAINABLE = 8,
+    FCDP_KERNEL_PROBE_STREAM = 9
 } fcdp_kernel_kind;
 fcdp_status fcdp_timing_enable(int32_t capacity);
 fcdp_status fcdp_timing_collect(int32_t kind, int64_t *launches, double *total_ms);
@@ -479,6 +480,19 @@ fcdp_status fcdp_timing_collect(int32_t kind, int64_t *launches, double *total_m
  * byte counters and to state the copy speed this GPU reaches. */
 fcdp_status fcdp_probe_copy(void *dst, const void *src, size_t bytes,
                             fcdp_stream stream);
+
+/* The gradient-shard sum's mix of G reads to 1 write as ONE contiguous
+ * stream, the known-pattern reference next to which the reduce kernels are
+ * measured: tile t of dst (1024 elements) is the sum, in order, of the G
+ * consecutive 1024-element sub-tiles of src that start at element
+ * t * G * 1024, stored as soon as it is summed (same loads, adds and stores
+ * per output element as the one-tile-per-workgroup reduce kernel).
+ *   src    dev ptr, G * count fp32 elements
+ *   dst    dev ptr, count elements of dtype `out`; must not overlap src
+ *   count  a multiple of 1024 (else FCDP_EINVAL) */
+fcdp_status fcdp_probe_reduce_stream(void *dst, const void *src, int32_t G,
+                                     int64_t count, fcdp_dtype out,
+                                     fcdp_stream stream);
 
 #ifdef __cplusplus
 }

@@ -18,4 +18,5 @@ from .binding import (  # noqa: F401
     library_path, pointer_array, fcdp_timing_enable, fcdp_timing_collect,
     KERNEL_UNFLATTEN, KERNEL_UNFLATTEN_ZEROCOPY, KERNEL_FLATTEN, KERNEL_REDUCE,
     KERNEL_PACK, KERNEL_UNPACK, KERNEL_STORE_ZEROCOPY, KERNEL_PROBE_COPY, KERNEL_REDUCE_TRAINABLE,
+    KERNEL_PROBE_STREAM, fcdp_probe_reduce_stream,
 )

@@ -54,7 +54,7 @@ EXPORTS = [
     "fcdp_cache_state_set_tau", "fcdp_cache_state_place",
     "fcdp_cache_state_release", "fcdp_link_bytes",
     "fcdp_status_string", "fcdp_last_error", "fcdp_tuning_set",
-    "fcdp_tuning_get", "fcdp_probe_copy", "fcdp_timing_enable",
+    "fcdp_tuning_get", "fcdp_probe_copy", "fcdp_probe_reduce_stream", "fcdp_timing_enable",
     "fcdp_timing_collect",
 ]
 
@@ -134,6 +134,7 @@ def load_library() -> ctypes.CDLL:
     lib.fcdp_tuning_get.argtypes = [c.c_char_p]
     lib.fcdp_tuning_get.restype = i64
     lib.fcdp_probe_copy.argtypes = [vp, vp, c.c_size_t, vp]
+    lib.fcdp_probe_reduce_stream.argtypes = [vp, vp, i32, i64, c.c_int, vp]
     lib.fcdp_timing_enable.argtypes = [i32]
     lib.fcdp_timing_collect.argtypes = [i32, c.POINTER(i64), c.POINTER(c.c_double)]
     _lib = lib
@@ -435,6 +436,7 @@ KERNEL_UNPACK = 5
 KERNEL_STORE_ZEROCOPY = 6
 KERNEL_PROBE_COPY = 7
 KERNEL_REDUCE_TRAINABLE = 8
+KERNEL_PROBE_STREAM = 9
 
 
 def fcdp_timing_enable(capacity: int) -> None:
@@ -452,3 +454,8 @@ def fcdp_timing_collect(kind: int):
 def fcdp_probe_copy(dst, src, nbytes: int, stream=None) -> None:
     _check(load_library().fcdp_probe_copy(_ptr(dst), _ptr(src), nbytes,
                                           _stream(stream)))
+
+
+def fcdp_probe_reduce_stream(dst, src, G: int, count: int, out_dtype: int, stream=None) -> None:
+    _check(load_library().fcdp_probe_reduce_stream(_ptr(dst), _ptr(src), G, count, out_dtype,
+                                                   _stream(stream)))

@@ -1182,6 +1182,27 @@ try {
     return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_probe_copy: out of host memory");
 }
 
+fcdp_status fcdp_probe_reduce_stream(void *dst, const void *src, int32_t G, int64_t count,
+                                     fcdp_dtype out, fcdp_stream stream)
+try {
+    const char *fn = "fcdp_probe_reduce_stream";
+    if (!dst || !src) return fail(FCDP_EINVAL, std::string(fn) + ": NULL buffer");
+    if (!aligned16(dst) || !aligned16(src)) return fail(FCDP_EALIGN, std::string(fn) + ": buffer not 16-byte aligned");
+    if (G < 1) return fail(FCDP_EINVAL, std::string(fn) + ": G must be >= 1");
+    if (G > FCDP_MAX_G) return fail(FCDP_ESIZE, std::string(fn) + ": G exceeds FCDP_MAX_G (64)");
+    if (count < 0 || count % 1024) return fail(FCDP_EINVAL, std::string(fn) + ": count must be a non-negative multiple of 1024");
+    if (out != FCDP_BF16 && out != FCDP_F32) return fail(FCDP_EINVAL, std::string(fn) + ": unknown dtype");
+    const char *s0 = static_cast<const char *>(src), *d0 = static_cast<const char *>(dst);
+    if (count > 0 && s0 < d0 + count * (out == FCDP_F32 ? 4 : 2) && d0 < s0 + static_cast<int64_t>(G) * count * 4)
+        return fail(FCDP_EINVAL, std::string(fn) + ": dst overlaps src");
+    hipError_t e = static_cast<hipError_t>(fcdp::launch_reduce_stream_calibration(
+        dst, src, G, count, out, stream, count > 0 ? timing_events(FCDP_KERNEL_PROBE_STREAM) : fcdp::LaunchEvents()));
+    if (e != hipSuccess) return hip_fail(e, "launch reduce calibration stream");
+    return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_probe_reduce_stream: out of host memory");
+}
+
 fcdp_status fcdp_timing_enable(int32_t capacity)
 try {
     if (capacity < 0 || capacity > (1 << 20)) return fail(FCDP_EINVAL, "fcdp_timing_enable: capacity must be in 0..2^20");

@@ -162,6 +162,8 @@ struct ReduceRuns {
 int launch_reduce_runs(const void *const *partials, int32_t G, const ReduceRuns &runs,
                        int in_dtype, int out_dtype, float scale, void *out, void *stream,
                        const LaunchEvents &ev = LaunchEvents());
+int launch_reduce_stream_calibration(void *dst, const void *src, int32_t G, int64_t count,
+                                     int out_dtype, void *stream, const LaunchEvents &ev = LaunchEvents());
 int launch_plain_copy(void *dst, const void *src, size_t bytes, void *stream,
                       const PlainCopy &shape = PlainCopy());
 // dst 16-byte aligned, bytes even; max_wgs 0 = up to 16384 workgroups

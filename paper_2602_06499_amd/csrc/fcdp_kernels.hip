@@ -408,6 +408,56 @@ __global__ void __launch_bounds__(256) reduce_ranks(const ReduceArgs a)
     }
 }
 
+// ---- calibration stream for the reduce ----------------------------------
+// The reduce's G : 1 mix of reads and writes from ONE contiguous buffer: tile
+// t (1024 elements of output, one workgroup of 64 threads, four vectors per
+// lane as in reduce_ranks) sums the G consecutive 4 KiB sub-tiles that start
+// at element t * G * 1024 of src, in order, and stores the tile as soon as it
+// is summed.  Same loads, adds and stores per output element as reduce_ranks;
+// what differs is the address pattern (one stream instead of G), so its rate
+// is the ceiling of that kernel design for a given G.
+struct StreamArgs {
+    const char *src;
+    char *out;
+    int64_t tiles;
+    int32_t G;
+};
+
+template <bool OUT_F32>
+__global__ void __launch_bounds__(64) reduce_stream_calibration(const StreamArgs a)
+{
+    constexpr int kVecPerTile = 256; // 64 lanes x 4 vectors
+    for (int64_t t = blockIdx.x; t < a.tiles; t += gridDim.x) {
+        float acc[4][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[u][c] = -0.0f;
+        const char *base = a.src + t * a.G * (kVecPerTile * 16);
+        for (int g0 = 0; g0 < a.G; g0 += kGroup) {
+            float v[kGroup][4][4];
+#pragma unroll
+            for (int k = 0; k < kGroup; ++k) {
+                const int g = g0 + k < a.G ? g0 + k : a.G - 1; // clamp: the load is issued, the add is not
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    load4<true, true, kReduceNT>(base + static_cast<int64_t>(g) * (kVecPerTile * 16),
+                                                 u * 64 + threadIdx.x, v[k][u]);
+            }
+#pragma unroll
+            for (int k = 0; k < kGroup; ++k)
+                if (g0 + k < a.G)
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) acc[u][c] = acc[u][c] + v[k][u][c];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            store4<OUT_F32, kReduceNTStore>(a.out, t * kVecPerTile + u * 64 + threadIdx.x, acc[u]);
+    }
+}
+
 // ---- phased reduce: reads and writes kept apart in time -------------------
 // Measured on MI355X: a read stream of G partials runs at 7.0 TB/s, and the
 // same stream with the output written as it is produced at 6.0 TB/s, although
@@ -908,6 +958,21 @@ int launch_plain_copy(void *dst, const void *src, size_t bytes, void *stream,
     if (unroll >= 4) return launch_plain_h<4>(pa, g, b, hint, st, shape.ev);
     if (unroll >= 2) return launch_plain_h<2>(pa, g, b, hint, st, shape.ev);
     return launch_plain_h<1>(pa, g, b, hint, st, shape.ev);
+}
+
+int launch_reduce_stream_calibration(void *dst, const void *src, int32_t G, int64_t count,
+                                     int out_dtype, void *stream, const LaunchEvents &ev)
+{
+    if (count <= 0) return hipSuccess;
+    StreamArgs a;
+    a.src = static_cast<const char *>(src);
+    a.out = static_cast<char *>(dst);
+    a.tiles = count / 1024;
+    a.G = G;
+    const dim3 grid(static_cast<unsigned>(std::min<int64_t>(a.tiles, 0x7fffffff))), block(64);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (out_dtype == FCDP_F32) return launch_one(reduce_stream_calibration<true>, grid, block, st, ev, a);
+    return launch_one(reduce_stream_calibration<false>, grid, block, st, ev, a);
 }
 
 int launch_reduce(const void *const *partials, int32_t G, int64_t elem_offset,

@@ -220,6 +220,16 @@ def main():
             check_reduce(G, count, e0, in_dt, out_dt, 0)
             check_reduce(G, count, e0, in_dt, out_dt, 0, float(np.float32(1.0 / G)))
             n += 2
+    for G, tiles in ((1, 2), (5, 7), (8, 3), (19, 2), (64, 1)):
+        print("calibration stream", G, tiles, flush=True)
+        src = synth.rng(0, G, synth.KIND_GRAD, 3).standard_normal((tiles, G, 1024), dtype=np.float32)
+        parts = [np.ascontiguousarray(src[:, r, :]).reshape(-1) for r in range(G)]
+        for out_dt in (oracle.F32, oracle.BF16):
+            d_out = Buf(tiles * 1024 * (4 if out_dt == oracle.F32 else 2))
+            fcdp.fcdp_probe_reduce_stream(d_out, dev(src), G, tiles * 1024, out_dt, None)
+            got = d_out.view(np.uint32 if out_dt == oracle.F32 else np.uint16)
+            assert np.array_equal(got, oracle.reduce(parts, 0, tiles * 1024, out_dt).view(got.dtype)), (G, tiles)
+        n += 1
     for name, sizes, tr, G, esz in PEFT_CASES():
         print("peft", name, flush=True)
         check_peft(name, sizes, tr, G, esz)

@@ -47,3 +47,26 @@ def test_product_never_imports_the_oracle():
     head, _, tail = bench.partition("if not args.no_cpu_baseline:")
     assert "import oracle" not in head, "bench.py may import the oracle only in its cpu_baseline leg"
     assert "import oracle" in tail
+
+
+def test_traffic_figures_in_the_bench_line_are_those_of_the_profile():
+    """bench.py prints roofline.traffic from a table, not from counters of its
+    own run; the table must be the totals of the counter summary it names."""
+    import importlib.util
+    import re
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    path = os.path.join(ROOT, bench.TRAFFIC_SOURCE)
+    assert os.path.exists(path), "the profile the bench line cites is missing"
+    totals = {}
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 9 and cells[0] in bench.MEASURED_TRAFFIC:
+            m = re.match(r"\*{0,2}([0-9.]+) MB\*{0,2}$", cells[6])
+            if m:
+                totals[(cells[0], cells[1])] = float(m.group(1)) * 1e6
+    for cfg, (k1, k3f, k3b) in bench.MEASURED_TRAFFIC.items():
+        assert totals[(cfg, "K1 unflatten")] == k1, cfg
+        assert totals[(cfg, "K3 fp32 -> fp32")] == k3f, cfg
+        assert totals[(cfg, "K3 fp32 -> bf16")] == k3b, cfg

@@ -397,6 +397,27 @@ def test_reduce_phased_specials_in_place_and_both_kernels_agree():
         fcdp.fcdp_tuning_set("reduce_phased", before)
 
 
+@pytest.mark.parametrize("G,tiles,out_dt", [(1, 3, oracle.F32), (5, 17, oracle.F32), (8, 64, oracle.BF16),
+                                            (19, 9, oracle.F32), (32, 33, oracle.BF16), (64, 5, oracle.F32)])
+def test_reduce_calibration_stream_is_the_same_sum(G, tiles, out_dt):
+    """The measurement probe fcdp_probe_reduce_stream sums, per 1024-element
+    tile, the G consecutive sub-tiles of one buffer in order: against the
+    oracle's rank-order sum of the G de-interleaved partials."""
+    g = synth.rng(0, 600 + G, synth.KIND_GRAD, tiles)
+    src = (g.standard_normal((tiles, G, 1024), dtype=np.float32) * np.float32(1e-3))
+    parts = [np.ascontiguousarray(src[:, r, :]).reshape(-1) for r in range(G)]
+    count = tiles * 1024
+    want = oracle.reduce(parts, 0, count, out_dt)
+    d_src = to_dev(src)
+    out = Arena([count * (4 if out_dt == oracle.F32 else 2)])
+    fcdp.fcdp_probe_reduce_stream(out.ptr(0), d_src, G, count, out_dt, None)
+    torch.cuda.synchronize()
+    _cmp_reduce(out.get(0, np.float32 if out_dt == oracle.F32 else np.uint16), want, out_dt)
+    out.check_guards()
+    with pytest.raises(fcdp.FcdpError):
+        fcdp.fcdp_probe_reduce_stream(out.ptr(0), d_src, G, count - 1, out_dt, None)
+
+
 PACK_CASES = [
     ("lora_like", [4096, 160, 160, 4096, 160, 160, 9000, 64], [0, 1, 1, 0, 1, 1, 0, 0], 8, 2),
     ("odd", [1001, 3, 777, 0, 12345, 1], [1, 0, 1, 1, 0, 1], 3, 2),
