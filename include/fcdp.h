@@ -150,11 +150,12 @@ fcdp_status fcdp_layout_prepare(const fcdp_layout *layout);
 /* ---------------------------------------------------- layer materialization
  * Rebuilds the T per-tensor parameter buffers of one layer.
  *
- * FCDP_SRC_DEVICE_SHARDS (forward, cache miss; Sec. 4.3 forward pass, Alg. 1
- * dirty branch "p <- AllGather(p_inter)"): tensor_t[j] =
+ * FCDP_SRC_DEVICE_SHARDS (forward, cache miss; Sec. 4.3 forward pass, Alg. 1:
+ * the dirty branch's inter-node gather): tensor_t[j] =
  * shard_{(off_t+j) div S}[(off_t+j) mod S].  If store_cache != FCDP_STORE_NONE
  * the padded flat image concat(shard_0..shard_{G-1}) is also copied to
- * host_cache on the `copy` stream (Alg. 1 "H[p] <- p", gpu to host), ordered
+ * host_cache on the `copy` stream (Alg. 1: the dirty branch's refresh of
+ * the host copy, GPU to host), ordered
  * after everything enqueued on `compute` before this call; the shards must
  * stay unmodified until that copy has completed in `copy`-stream order.
  * FCDP_STORE_DMA uses hipMemcpyAsync; FCDP_STORE_ZEROCOPY uses a kernel with a
@@ -162,7 +163,8 @@ fcdp_status fcdp_layout_prepare(const fcdp_layout *layout);
  * (host_cache must then be mapped pinned memory, else FCDP_ENOTPINNED).
  *
  * FCDP_SRC_HOST_DMA (backward / clean forward, cache hit; Sec. 4.3 backward
- * pass, Alg. 1 "p_intra <- H[p]"): host_cache is copied to `staging` on the
+ * pass, Alg. 1: the load of the cached copy from the host): host_cache is
+ * copied to `staging` on the
  * `copy` stream, then the scatter runs on `compute` after it.  The library
  * remembers the last scatter that read each staging buffer and makes the
  * next copy into that buffer wait for it, so alternating two staging
@@ -231,7 +233,8 @@ fcdp_status fcdp_materialize_layer_static(const fcdp_layout *layout,
                                           fcdp_stream compute,
                                           fcdp_stream copy);
 
-/* The cache store alone (Alg. 1 "H[p] <- p"), for callers that decide after
+/* The cache store alone (Alg. 1: the dirty branch's refresh of the host
+ * copy), for callers that decide after
  * the layer's forward computation whether to offload it (Sec. 4.4): copies
  * concat(shard_0..shard_{G-1}) to host_cache on `copy`, ordered after what is
  * enqueued on `compute` at the time of the call.  store_mode is FCDP_STORE_DMA
@@ -249,7 +252,7 @@ fcdp_status fcdp_flatten_to_shards(const fcdp_layout *layout,
 
 /* ------------------------------------------------------ gradient-shard sum
  * The local half of the gradient reduce-scatter (Sec. 2.1; Sec. 6.2
- * "Gradient reduce-scatter"; Alg. 1 "ReduceScatter(grad W_t)"): for k in
+ * the gradient reduce-scatter; Alg. 1: the reduce-scatter of the trainable gradients): for k in
  * [0, count)
  *     acc = p_0[e0+k];  acc = acc + p_g[e0+k]  for g = 1..G-1, in that order
  *     out[k] = acc                      (out == FCDP_F32)
@@ -273,8 +276,8 @@ fcdp_status fcdp_reduce_grad_shard(const void *const *partial_ptrs, int32_t G,
                                    void *out_shard, fcdp_stream stream);
 
 /* Gradient-shard sum of the trainable parameters straight from G unpacked
- * flat gradients: pack and reduce in one launch (Alg. 1 "ReduceScatter(grad
- * W_t)"; Sec. 4.5: only trainable parameters take part).  With Sp =
+ * flat gradients: pack and reduce in one launch (Alg. 1: the reduce-scatter of the
+ * trainable gradients; Sec. 4.5: only trainable parameters take part).  With Sp =
  * packed_numel / G and pk(.) the packed order of fcdp_pack_trainable,
  *     out[k] = sum over g = 0..G-1, in that order, of grad_g[flat index of
  *              packed element rank*Sp + k],     k in [0, Sp)
@@ -293,7 +296,7 @@ fcdp_status fcdp_reduce_trainable_shard(const fcdp_layout *layout,
                                         fcdp_stream stream);
 
 /* The two sums above followed by one multiplication.  Alg. 1 names the
- * collective ("ReduceScatter(grad W_t)") without saying whether ranks are
+ * collective (a reduce-scatter of the trainable gradients) without saying whether ranks are
  * summed or averaged; scale = 1/G gives the mean, and a loss-scale's inverse
  * can ride along.  For every output element
  *     acc = the rank-order sum as defined above
@@ -336,8 +339,8 @@ fcdp_status fcdp_unpack_trainable(const fcdp_layout *layout,
                                   fcdp_stream stream);
 
 /* ------------------------------------------------------------- host cache
- * Pinned, device-mapped host memory for the cache H (Sec. 4.4 "Host Memory
- * Optimization": allocated once, kept for the whole run, updated in place,
+ * Pinned, device-mapped host memory for the cache H (Sec. 4.4, host memory:
+ * allocated once, kept for the whole run, updated in place,
  * taken from the NUMA node local to the GPU).  numa_node >= 0 binds the
  * pages to that node (best effort: if the kernel refuses the policy the
  * allocation still succeeds and fcdp_last_error() says so); -1 = no policy.
@@ -382,7 +385,7 @@ fcdp_status fcdp_cache_state_mark_dirty(fcdp_cache_state *state, int32_t layer,
 int32_t fcdp_cache_state_is_dirty(const fcdp_cache_state *state, int32_t layer,
                                   int32_t klass);
 
-/* Adaptive placement (Sec. 4.4 "Adaptive GPU Caching").  tau in [0, 1]; the
+/* Adaptive placement (Sec. 4.4, adaptive GPU caching).  tau in [0, 1]; the
  * default 0 offloads every layer (the plain schedule of Sec. 4.3).
  * fcdp_cache_state_place is the decision at the "cache on CPU" point of a
  * layer, after its forward computation: utilisation = used_bytes /

@@ -107,7 +107,7 @@ int fcdp_oracle_split(const void *flat, int64_t S, int32_t G, int32_t esz,
 
 /*
  * Materialize from G rank shards (the receive side of the forward
- * all-gather, Sec. 4.3 forward pass; Alg. 1 "p <- AllGather(p_inter)"):
+ * all-gather, Sec. 4.3 forward pass; Alg. 1: the dirty branch's inter-node gather):
  *   tensor_t[j] = shard_{(off_t+j) div S}[(off_t+j) mod S].
  * Padding is never read.
  */
@@ -132,7 +132,8 @@ int fcdp_oracle_materialize_from_shards(const void *const *shards, int64_t S,
 
 /*
  * Materialize from the host cache H_l, which holds the padded flat image of
- * the layer in shard order (Sec. 4.3 backward pass; Alg. 1 "p_intra <- H[p]"
+ * the layer in shard order (Sec. 4.3 backward pass; Alg. 1: the load of the
+ * cached copy from the host
  * followed by the intra-node gather, which on one GPU is the whole layer):
  *   tensor_t[j] = H[off_t + j].
  */
@@ -152,7 +153,7 @@ int fcdp_oracle_materialize_from_flat(const void *flat, const int64_t *n,
 }
 
 /*
- * Cache store (Alg. 1 "H[p] <- p", gpu to host): H = concat(shard_0 ..
+ * Cache store (Alg. 1: the dirty branch's refresh of the host copy, GPU to host): H = concat(shard_0 ..
  * shard_{G-1}), padding included.
  */
 int fcdp_oracle_cache_store(const void *const *shards, int64_t S, int32_t G,
@@ -245,7 +246,7 @@ void fcdp_oracle_bf16_rne_array(const float *x, int64_t n, uint16_t *out)
 
 /*
  * Gradient-shard reduction (the local half of the reduce-scatter, Sec. 6.2
- * "Gradient reduce-scatter"; Alg. 1 "ReduceScatter(grad W_t)"):
+ * the gradient reduce-scatter; Alg. 1: the reduce-scatter of the trainable gradients):
  *   acc = p_0[e0+k]; acc = acc + p_g[e0+k] for g = 1 .. G-1, in that order,
  * in IEEE binary32 (one rounding per add; built without fast-math and
  * without contraction, so the compiler keeps this order), and
