@@ -452,7 +452,13 @@ const char *fcdp_last_error(void);
  *                         cache on `copy`; a consumer that misses one of the
  *                         documented waits then reads NaNs instead of stale
  *                         bytes that may happen to be right.  Results are
- *                         unchanged; each call costs one more pass. */
+ *                         unchanged; each call costs one more pass.  With
+ *                         the knob on the data calls also look every device
+ *                         buffer up with hipMemGetAddressRange: one that does
+ *                         not lie inside a single allocation with at least
+ *                         the documented number of bytes is FCDP_ESIZE
+ *                         before anything is enqueued (no sizes cross this
+ *                         boundary, so normal operation cannot check them). */
 fcdp_status fcdp_tuning_set(const char *name, int64_t value);
 int64_t fcdp_tuning_get(const char *name); /* -1 if unknown */
 

@@ -42,6 +42,31 @@ fcdp_status hip_fail(hipError_t e, const char *what)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Debugging aid (tuning knob debug_poison): no sizes cross the boundary, so a
+// buffer that is too small cannot be refused in normal operation; with the
+// knob on, every device buffer a call is about to read or write is looked up
+// with hipMemGetAddressRange and must lie inside ONE allocation with at least
+// `bytes` bytes from `p` on.  A pointer the runtime cannot place (a mapped
+// host alias, a sub-range it does not track) is let through.  Catches the
+// mistakes a caller's own allocator does not hide: an allocation of the
+// wrong element size, a shard buffer sized S instead of N_pad, a short tail.
+fcdp_status check_extent(const void *p, size_t bytes, const char *fn, const char *what)
+{
+    if (!p || bytes == 0) return FCDP_OK;
+    hipDeviceptr_t base = nullptr;
+    size_t size = 0;
+    hipError_t e = hipMemGetAddressRange(&base, &size, const_cast<void *>(p));
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return FCDP_OK;
+    }
+    const size_t off = static_cast<size_t>(static_cast<const char *>(p) - static_cast<const char *>(base));
+    if (off > size || bytes > size - off)
+        return fail(FCDP_ESIZE, std::string(fn) + ": " + what + " needs " + std::to_string(bytes) +
+                                    " bytes but its allocation ends after " + std::to_string(size - std::min(off, size)));
+    return FCDP_OK;
+}
+
 // ----------------------------------------------------------------- events
 // A ring of timing-disabled events for "record on A, wait on B" edges, and a
 // small table that remembers, per staging buffer, the event recorded after
@@ -557,7 +582,15 @@ try {
     if ((st = tables_for_current_device(L, &tabs)) != FCDP_OK) return st;
     const fcdp::Tuning &tune = fcdp::tuning();
 
-    if (tune.debug_poison && (st = poison_tensors(L, tensor_ptrs, compute)) != FCDP_OK) return st;
+    if (tune.debug_poison) {
+        for (int32_t t = 0; t < L->T; ++t)
+            if ((st = check_extent(tensor_ptrs[t], static_cast<size_t>(L->numel[t]) * L->esz, fn, "a tensor")) != FCDP_OK) return st;
+        if (src == FCDP_SRC_DEVICE_SHARDS)
+            for (int32_t r = 0; r < L->G; ++r)
+                if ((st = check_extent(shard_ptrs[r], shard_bytes, fn, "a shard")) != FCDP_OK) return st;
+        if (src == FCDP_SRC_HOST_DMA && (st = check_extent(staging, flat_bytes, fn, "staging")) != FCDP_OK) return st;
+        if ((st = poison_tensors(L, tensor_ptrs, compute)) != FCDP_OK) return st;
+    }
 
     const void *small[FCDP_MAX_G];
     if (src == FCDP_SRC_DEVICE_SHARDS) {
@@ -769,6 +802,12 @@ try {
         if (overlap && !(pb == ob && ie == oe))
             return fail(FCDP_EINVAL, std::string(fn) + ": out_shard overlaps an input other than exactly in place");
     }
+    if (fcdp::tuning().debug_poison) {
+        fcdp_status st;
+        for (int32_t g = 0; g < G; ++g)
+            if ((st = check_extent(partial_ptrs[g], static_cast<size_t>(elem_offset + count) * ie, fn, "a partial")) != FCDP_OK) return st;
+        if ((st = check_extent(out_shard, static_cast<size_t>(count) * oe, fn, "out_shard")) != FCDP_OK) return st;
+    }
     hipError_t e = static_cast<hipError_t>(fcdp::launch_reduce(partial_ptrs, G, elem_offset, count, in, out, scale, out_shard, stream,
                                                                count > 0 ? timing_events(FCDP_KERNEL_REDUCE) : fcdp::LaunchEvents()));
     if (e != hipSuccess) return hip_fail(e, "launch reduce");
@@ -852,6 +891,11 @@ static fcdp_status pack_or_unpack(const fcdp_layout *L, const void *src, void *d
         return fail(FCDP_EINVAL, std::string(fn) + ": flat and packed overlap");
     const fcdp::PieceTable &tab = pack ? L->pack : L->unpack;
     if (tab.pieces.empty()) return FCDP_OK;
+    if (fcdp::tuning().debug_poison) {
+        fcdp_status ce;
+        if ((ce = check_extent(flat, static_cast<size_t>(fb), fn, "flat")) != FCDP_OK) return ce;
+        if ((ce = check_extent(packed, static_cast<size_t>(pb), fn, "packed")) != FCDP_OK) return ce;
+    }
     const fcdp::DeviceTables *tabs = nullptr;
     fcdp_status st = tables_for_current_device(L, &tabs);
     if (st != FCDP_OK) return st;

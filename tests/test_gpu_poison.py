@@ -96,3 +96,45 @@ def test_poison_is_written_first(poison):
     out.check_guards()
     staging.check_guards()
     H.free()
+
+
+def test_debug_mode_refuses_buffers_that_are_too_small(poison):
+    """No sizes cross the C boundary; with debug_poison on the library looks
+    each device buffer up in the runtime's allocation table and refuses one
+    that ends before the documented size (FCDP_ESIZE, nothing enqueued).
+    Buffers here come straight from hipMalloc, one allocation each, so the
+    short one really is short."""
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipMalloc.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_size_t]
+    hip.hipFree.argtypes = [ctypes.c_void_p]
+
+    def dmalloc(nbytes):
+        p = ctypes.c_void_p()
+        assert hip.hipMalloc(ctypes.byref(p), nbytes) == 0
+        return p.value
+
+    sizes, G = [4096, 1000], 2
+    L = fcdp.fcdp_layout_build(sizes, None, G, 2)
+    L.prepare()
+    S = L.shard_numel
+    shards = [dmalloc(S * 2) for _ in range(G)]
+    good = [dmalloc(k * 2) for k in sizes]
+    short = [good[0], dmalloc(sizes[1] * 2 - 512)]       # 256 elements short
+    torch.cuda.synchronize()
+    with pytest.raises(fcdp.FcdpError) as e:
+        fcdp.fcdp_materialize_layer(L, fcdp.SRC_DEVICE_SHARDS, shards, None, None, short)
+    assert e.value.name == "FCDP_ESIZE" and "a tensor" in str(e.value)
+    with pytest.raises(fcdp.FcdpError) as e:
+        fcdp.fcdp_materialize_layer(L, fcdp.SRC_DEVICE_SHARDS, [shards[0], short[1]], None, None, good)
+    assert e.value.name == "FCDP_ESIZE" and "a shard" in str(e.value)
+    fcdp.fcdp_materialize_layer(L, fcdp.SRC_DEVICE_SHARDS, shards, None, None, good)   # right sizes pass
+    parts = [dmalloc(4000 * 4), dmalloc(4000 * 4 - 256)]
+    out = dmalloc(4000 * 4)
+    with pytest.raises(fcdp.FcdpError) as e:
+        fcdp.fcdp_reduce_grad_shard(parts, 2, 0, 4000, fcdp.F32, fcdp.F32, out)
+    assert e.value.name == "FCDP_ESIZE" and "a partial" in str(e.value)
+    fcdp.fcdp_reduce_grad_shard(parts, 2, 0, 3900, fcdp.F32, fcdp.F32, out)              # fits: passes
+    torch.cuda.synchronize()
+    for p in shards + good + [short[1], out] + parts:
+        hip.hipFree(p)
