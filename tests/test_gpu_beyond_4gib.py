@@ -68,6 +68,17 @@ def test_layer_with_tensors_and_shards_beyond_4gib():
     torch.cuda.synchronize()
     for t, k in enumerate(sizes):
         _same(tensors[t][:k], flat[off[t]:off[t] + k], "device shards, tensor %d" % t)
+    # the oracle's own index arithmetic at these sizes: its (tensor x shard) segment list
+    # says which window of which shard every piece of a tensor comes from; check the first
+    # and last 4096 elements of every segment (they straddle the 4 GiB lines) against it
+    segs = oracle.segments(sizes, G)
+    assert int(segs[:, 4].sum()) == N
+    for t_, r_, dst_off, src_off, length in segs.tolist():
+        for a in sorted({0, max(0, length - 4096)}):
+            n = min(4096, length - a)
+            got = tensors[t_][dst_off + a:dst_off + a + n]
+            want = flat[r_ * S + src_off + a:r_ * S + src_off + a + n]
+            assert torch.equal(got, want), ("oracle segment", t_, r_, a)
     hc = torch.from_numpy(H.numpy(np.int16, Np))
     for lo in range(0, Np, 1 << 29):              # compare in 1 GiB slabs
         hi = min(Np, lo + (1 << 29))
@@ -115,9 +126,13 @@ def test_layer_with_tensors_and_shards_beyond_4gib():
     H.free()
 
 
-def test_gradient_slices_beyond_4gib():
+@pytest.mark.parametrize("e0", [5, 8], ids=["one_tile_per_workgroup", "phased_40_phases"])
+def test_gradient_slices_beyond_4gib(e0):
+    """e0 = 5 leaves the slices unaligned (the one-tile-per-workgroup kernel);
+    e0 = 8 keeps them 16-byte aligned, so the phased kernel runs, 40 phases
+    long at this size."""
     dev = torch.device("cuda:0")
-    G, count, e0 = 3, 2 ** 30 + 4099, 5           # 4 GiB + 16 KiB of fp32 per rank
+    G, count = 3, 2 ** 30 + 4099                   # 4 GiB + 16 KiB of fp32 per rank
     parts = [torch.empty(e0 + count + 3, dtype=torch.float32, device=dev) for _ in range(G)]
     for r, p in enumerate(parts):
         _fill_random(p, 77 + r)
