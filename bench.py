@@ -86,7 +86,8 @@ def parse():
     ap.add_argument("--cpu-sample-layers", type=int, default=3)
     ap.add_argument("--cpu-threads", type=int, default=4,
                     help="threads of the all-threads oracle leg (one layer each)")
-    ap.add_argument("--probe-gib", type=int, default=2, help="size of the host-link probe copy")
+    ap.add_argument("--probe-gib", type=int, default=16,
+                    help="size of the host-link probe copy (16: the transfer size of the paper's Table 3, first row)")
     ap.add_argument("--reduce-study", action="store_true",
                     help="instead of the benchmark: the gradient-shard reduce at the 7B / 13B / 70B shard sizes "
                          "(G = 8, 16, 32) with both kernels, next to the G:1 calibration stream and a read-only "
@@ -759,6 +760,9 @@ def main():
                       "frac_d2h": round(head["d2h_gbps"] / LINK_PEAK_GBPS, 4),
                       "frac_h2d": round(head["h2d_gbps"] / LINK_PEAK_GBPS, 4),
                       "probe_h2d": round(link["h2d"], 2), "probe_d2h": round(link["d2h"], 2),
+                      "probe_bytes": probe_bytes,
+                      # the paper's Table 3, first row: one 16 GB host-to-device transfer over the link
+                      "probe_h2d_seconds_per_16e9_bytes": round(16e9 / (link["h2d"] * 1e9), 4),
                       "backward_ms_per_layer": round(head["bwd_ms"] / L, 3),
                       # backward sweep per layer against the longer of its two parts
                       "backward_overlap_efficiency": round(

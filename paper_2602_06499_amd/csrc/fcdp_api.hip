@@ -679,13 +679,13 @@ try {
         return fail(FCDP_ESIZE, "device ordinal beyond 15 is not supported");
     StaticCtx &c = g_static[dev];
     const fcdp::DeviceTables *tabs = tables_if_prepared(L, dev);
+    std::lock_guard<std::mutex> lk(c.mu);
     if (!tabs || !c.ready)
         return fail(FCDP_ESTATE, std::string(fn) + ": call fcdp_layout_prepare for this layout on this device first "
                                                    "(this entry point uploads and allocates nothing)");
     hipStream_t compute = static_cast<hipStream_t>(compute_);
     hipStream_t copy = static_cast<hipStream_t>(copy_);
     const fcdp::Tuning &tune = fcdp::tuning();
-    std::lock_guard<std::mutex> lk(c.mu);
     // the array may still be read by the scatter of the previous call
     if (c.read_recorded) FCDP_HIP(hipStreamWaitEvent(copy, c.read_done, 0), "hipStreamWaitEvent(scratch)");
     FCDP_HIP(hipMemcpyAsync(c.ptr, host_cache, flat_bytes, hipMemcpyHostToDevice, copy), "hipMemcpyAsync(H2D)");
