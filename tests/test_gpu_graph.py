@@ -77,3 +77,51 @@ def test_graph_replays_match_the_oracle():
         assert np.array_equal(packed.get(0, np.uint16), want[2]), version
         gshard.check_guards()
         packed.check_guards()
+
+
+def test_phased_reduce_in_a_graph():
+    """The phased reduce (a persistent grid whose launch shape depends on the
+    device's compute-unit count, read once on the host) is an ordinary kernel
+    launch: recorded into a graph, replayed four times with the partials
+    rewritten in between, every replay the oracle's bits."""
+    G, n = 5, 4194304 + 3 * 256 + 2
+    grads = Arena([n * 4] * G)
+    gshard = Arena([n * 4])
+    bshard = Arena([n * 2])
+    stream = torch.cuda.Stream()
+
+    def fill(version):
+        parts = [synth.grad_partial_f32(synth.CONFIGS["gpt2_small_g4"], 40 + version, r, n) for r in range(G)]
+        for r in range(G):
+            grads.fill(r, parts[r])
+        return oracle.reduce(parts, 0, n, oracle.F32), oracle.reduce(parts, 0, n, oracle.BF16, float(np.float32(0.2)))
+
+    def enqueue():
+        fcdp.fcdp_reduce_grad_shard(grads.ptrs(), G, 0, n, fcdp.F32, fcdp.F32, gshard.ptr(0), stream)
+        fcdp.fcdp_reduce_grad_shard_scaled(grads.ptrs(), G, 0, n, fcdp.F32, fcdp.BF16, float(np.float32(0.2)),
+                                           bshard.ptr(0), stream)
+
+    before = fcdp.fcdp_tuning_get("reduce_phased")
+    fcdp.fcdp_tuning_set("reduce_phased", 1)             # both launches take the phased kernel
+    try:
+        want = fill(0)
+        torch.cuda.synchronize()
+        enqueue()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream, capture_error_mode="thread_local"):
+            enqueue()
+    finally:
+        fcdp.fcdp_tuning_set("reduce_phased", before)
+    for version in range(4):
+        if version:
+            want = fill(version)
+        gshard.buf.fill_(0xC3)
+        bshard.buf.fill_(0xC3)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(gshard.get(0, np.uint32), want[0].view(np.uint32)), version
+        assert np.array_equal(bshard.get(0, np.uint16), want[1]), version
+        gshard.check_guards()
+        bshard.check_guards()
