@@ -435,8 +435,11 @@ const char *fcdp_last_error(void);
  *                         that the chip reads, then writes) whenever slices
  *                         and output are 16-byte aligned and at least 8 steps
  *                         per wave long; 2 the phased kernel where it measured
- *                         faster: G >= 12, or fp32 in and out with G >= 3 (2).
+ *                         faster, by G and the two element types (2).
  *                         The result is the same bits either way.
+ *   reduce_phase_waves    waves per SIMD of the phased kernel: 1 (104 steps
+ *                         held per wave; built for G a multiple of 8 only,
+ *                         other G take 2), 2 (52 steps), 0 by rule (0)
  *   link_max_wgs          workgroups of the zero-copy fetch / store kernels,
  *                         0 = no bound (64)
  *   link_block            their threads per workgroup (256)

@@ -17,6 +17,10 @@ HIPCC_FLAGS = [
     # keep fp32 adds as written: no packed-fp32 forms, no denormal flushing
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-fno-gpu-flush-denormals-to-zero", "-ffp-contract=off",
+    # the phased reduce keeps up to 416 sums per lane in registers, which needs its
+    # step loop unrolled in full (static register indices); past the default limit
+    # of 16 K instructions the compiler leaves the loop rolled and the sums in scratch
+    "-mllvm", "-pragma-unroll-threshold=200000",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 

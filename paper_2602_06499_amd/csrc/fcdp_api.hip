@@ -1181,6 +1181,9 @@ try {
     } else if (n == "reduce_phased") {
         if (v < 0 || v > 2) return fail(FCDP_EINVAL, "reduce_phased: 0, 1 or 2");
         t.reduce_phased = v;
+    } else if (n == "reduce_phase_waves") {
+        if (v < 0 || v > 2) return fail(FCDP_EINVAL, "reduce_phase_waves: 0, 1 or 2");
+        t.reduce_phase_waves = v;
     } else if (n == "debug_poison") {
         if (v != 0 && v != 1) return fail(FCDP_EINVAL, "debug_poison: 0 or 1");
         t.debug_poison = v;
@@ -1208,6 +1211,7 @@ int64_t fcdp_tuning_get(const char *name)
     if (n == "max_copies_in_flight") return t.max_copies_in_flight;
     if (n == "reduce_block") return t.reduce_block;
     if (n == "reduce_phased") return t.reduce_phased;
+    if (n == "reduce_phase_waves") return t.reduce_phase_waves;
     if (n == "debug_poison") return t.debug_poison;
     return -1;
 }

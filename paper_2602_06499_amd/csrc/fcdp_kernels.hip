@@ -464,30 +464,31 @@ __global__ void __launch_bounds__(64) reduce_stream_calibration(const StreamArgs
 // the output is only 3-11 % of the bytes: stores that trickle into a
 // read-dominated stream cost the memory system far more than their bytes.
 // Here the whole chip reads for a while and then writes for a while.  The
-// grid is persistent: two waves per SIMD, all resident at once, and every
-// wave owns one contiguous run of steps (a step = 64 lanes x one 4-element
-// vector).  A wave sums up to kPhaseSteps steps of every partial, keeps the
-// finished sums in registers (4 per step and lane) and stores them only
+// grid is persistent: ONE wave per SIMD, all resident at once, and every
+// wave owns one contiguous run of steps (a step = 64 lanes x one 16-byte
+// unit of each partial).  A wave sums up to 104 steps of every
+// partial, keeps the finished sums in registers (4 per fp32 step and lane;
+// with one wave per SIMD a lane has 512 registers, 256 of them accumulation
+// registers that the compiler uses as backing store) and stores them only
 // after its last load of the phase.  All waves have the same work, so they
 // reach their stores at about the same time and the stores arrive at the
-// memory as one burst.  With kPhaseSteps = 52 one phase holds 2048 waves x
-// 52 KiB = 109 MB of fp32 sums on a 256-CU part, i.e. the whole shard of
-// every Llama-shaped layer here; longer inputs take several phases.  Giving
-// each wave a contiguous run (rather than dealing steps round robin) and
-// holding more steps per wave both measured faster: 16 steps at four waves
-// per SIMD reaches 6.4 TB/s at G = 32, 48 steps at two waves 6.8 TB/s.
-// The adds per element stay in rank order, one wave and lane owns an element
-// from its first load to its store, and the launch shape changes nothing in
-// the result.
-#ifndef FCDP_PHASE_STEPS
-#define FCDP_PHASE_STEPS 52
-#endif
-#ifndef FCDP_PHASE_WAVES_PER_EU
-#define FCDP_PHASE_WAVES_PER_EU 2
-#endif
-constexpr int kPhaseSteps = FCDP_PHASE_STEPS;              // steps of 4 elements per lane held per phase
+// memory as one burst.  With 104 steps one phase holds 1024 waves x
+// 104 KiB = 109 MB of fp32 sums on a 256-CU part, i.e. the whole shard of
+// every Llama-shaped layer here; longer inputs take several phases.  Fewer,
+// fatter waves measured faster at every step of the way (G = 32, fp32 out,
+// fraction of the HBM peak): 16 steps at four waves per SIMD 0.80, 24 at
+// three 0.83, 48 at two 0.85, 96 at one 0.87; so did a contiguous run per
+// wave against steps dealt round robin.  The adds per element stay in rank
+// order, one wave and lane owns an element from its first load to its
+// store, and the launch shape changes nothing in the result.
+// Two shapes of the same kernel are built: one wave per SIMD holding 104 steps
+// (416 sums per lane), and two waves per SIMD holding 52 steps each.  The
+// first is the faster one when every load group is full (G a multiple of 8):
+// with a single wave on a SIMD nothing hides the round trip of a short last
+// group (measured at a 25 M-element shard: G = 16 0.85 of the peak, G = 9 0.74,
+// G = 1 0.33), which the second wave of the other shape does.
 constexpr int kPhasedBlock = 256;                          // four waves
-constexpr int kPhasedWavesPerSimd = FCDP_PHASE_WAVES_PER_EU;
+constexpr int kPhaseSteps1 = 104, kPhaseSteps2 = 52;       // steps of 4 elements per lane held per phase
 constexpr int kPhasedMinStepsPerWave = 8; // below this the one-tile-per-workgroup kernel is used
 #ifndef FCDP_PHASE_GROUP
 #define FCDP_PHASE_GROUP 8
@@ -563,14 +564,15 @@ __device__ __forceinline__ void add_group1(const ReduceArgs &a, int g0, int64_t 
 
 // Needs 16-byte aligned input slices and output (the launcher falls back to
 // reduce_ranks otherwise).  A unit is 16 bytes of input = E elements; a step
-// is 64 units, one per lane; a wave holds up to STEPS = kPhaseSteps * 4 / E
-// steps, i.e. kPhaseSteps * 4 sums per lane whatever the input type.
-template <int REM, bool IN_F32, bool OUT_F32, bool NT>
-__global__ void __launch_bounds__(kPhasedBlock, FCDP_PHASE_WAVES_PER_EU) // threads, waves per SIMD
+// is 64 units, one per lane; a wave holds up to STEPS = STEPS4 * 4 / E
+// steps, i.e. STEPS4 * 4 sums per lane whatever the input type.  WPE = waves
+// per SIMD the register budget is cut for (1: 512 registers, 2: 256).
+template <int STEPS4, int WPE, int REM, bool IN_F32, bool OUT_F32, bool NT>
+__global__ void __launch_bounds__(kPhasedBlock, WPE) // threads, waves per SIMD
 reduce_phased(const ReduceArgs a)
 {
     constexpr int E = IN_F32 ? 4 : 8;
-    constexpr int STEPS = kPhaseSteps * 4 / E;
+    constexpr int STEPS = STEPS4 * 4 / E;
     const int64_t n_units = a.count / E;
     const int64_t n_steps = (n_units + 63) >> 6;
     const int64_t w = static_cast<int64_t>(blockIdx.x) * (kPhasedBlock / 64) +
@@ -785,15 +787,18 @@ hipError_t launch_phased_r(const ReduceArgs &args, dim3 grid, dim3 block, hipStr
                            const LaunchEvents &ev)
 {
     if constexpr (REM < kPhasedGroup)
-        return launch_one(reduce_phased<REM, IN_F32, OUT_F32, kReduceNT>, grid, block, st, ev, args);
+        return launch_one(reduce_phased<kPhaseSteps2, 2, REM, IN_F32, OUT_F32, kReduceNT>, grid, block, st, ev, args);
     else
         return hipErrorInvalidValue; // not reachable: REM = G mod kPhasedGroup
 }
 
+// waves_per_simd 1: only built for G a multiple of the load group
 template <bool IN_F32, bool OUT_F32>
-hipError_t launch_phased_t(const ReduceArgs &args, dim3 grid, dim3 block, hipStream_t st,
+hipError_t launch_phased_t(const ReduceArgs &args, int waves_per_simd, dim3 grid, dim3 block, hipStream_t st,
                            const LaunchEvents &ev)
 {
+    if (waves_per_simd == 1)
+        return launch_one(reduce_phased<kPhaseSteps1, 1, 0, IN_F32, OUT_F32, kReduceNT>, grid, block, st, ev, args);
     switch (args.G % kPhasedGroup) {
     case 0: return launch_phased_r<0, IN_F32, OUT_F32>(args, grid, block, st, ev);
     case 1: return launch_phased_r<1, IN_F32, OUT_F32>(args, grid, block, st, ev);
@@ -999,28 +1004,39 @@ int launch_reduce(const void *const *partials, int32_t G, int64_t elem_offset,
     const int64_t nvec = count >> 2;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool inf = in_dtype == FCDP_F32, outf = out_dtype == FCDP_F32;
-    // the persistent grid: every wave resident at once
+    // the persistent grid: every wave resident at once.  Where each kernel pays (30
+    // launches each on MI355X, a 25 M-element shard, G = 1..64, all four type pairs,
+    // fractions of the HBM peak): with G a multiple of 8 the one-wave-per-SIMD shape
+    // beats one tile per workgroup for an fp32 shard from G = 8 on (0.86 against 0.78
+    // at G = 8, 16 and 32) and for a bf16 shard from G = 16 on (0.82-0.84 against
+    // 0.81); otherwise the two-wave shape does for fp32 partials into an fp32 shard
+    // from G = 3 on (+1 to +9 points) and for every other type pair from G = 12 on
+    // (+1 to +5); below that one tile per workgroup is 1-4 points faster.
     const int64_t wpb = kPhasedBlock / 64;
     const int64_t epu = inf ? 4 : 8;                       // elements per 16-byte unit
-    const int64_t steps_cap = kPhaseSteps * 4 / epu;       // steps a wave holds per phase
     const int64_t n_steps = (count / epu + 63) / 64;
-    const int64_t W = static_cast<int64_t>(device_cu_count()) * 4 * kPhasedWavesPerSimd;
-    // Where it pays (30 launches each on MI355X, a 25 M-element shard, G = 1..64,
-    // all four type pairs): fp32 partials into an fp32 shard from G = 3 on
-    // (+1 to +9 % of the HBM peak), every other type pair from G = 12 on (+1
-    // to +5 %); below that the one-tile-per-workgroup kernel is 1-4 % faster.
-    const bool pays = t.reduce_phased == 1 || (t.reduce_phased == 2 && (G >= 12 || (G >= 3 && inf && outf)));
-    if (pays && aligned && (reinterpret_cast<uintptr_t>(out) & 15u) == 0 &&
+    int wps = 0;                                           // waves per SIMD; 0 = not phased
+    if (t.reduce_phased == 1) {
+        wps = t.reduce_phase_waves ? static_cast<int>(t.reduce_phase_waves) : (G % kPhasedGroup == 0 ? 1 : 2);
+    } else if (t.reduce_phased == 2) {
+        if (G % kPhasedGroup == 0 && (outf ? G >= 8 : G >= 16)) wps = 1;
+        else if (G % kPhasedGroup != 0 && (G >= 12 || (G >= 3 && inf && outf))) wps = 2;
+        if (wps && t.reduce_phase_waves) wps = static_cast<int>(t.reduce_phase_waves);
+    }
+    if (wps == 1 && G % kPhasedGroup != 0) wps = 2;        // the one-wave shape is built for full groups only
+    const int64_t W = static_cast<int64_t>(device_cu_count()) * 4 * (wps ? wps : 1);
+    if (wps && aligned && (reinterpret_cast<uintptr_t>(out) & 15u) == 0 &&
         n_steps >= W * kPhasedMinStepsPerWave) {
+        const int64_t steps_cap = (wps == 1 ? kPhaseSteps1 : kPhaseSteps2) * 4 / epu; // steps a wave holds per phase
         const int64_t phases = (n_steps + W * steps_cap - 1) / (W * steps_cap);
         if (phases > 0x7fffffff) return hipErrorInvalidValue;
         args.phases = static_cast<int32_t>(phases);
         args.spp = static_cast<int32_t>((n_steps + W * phases - 1) / (W * phases)); // <= steps_cap
         const dim3 g(static_cast<unsigned>(W / wpb)), b(kPhasedBlock);
-        if (inf && outf) return launch_phased_t<true, true>(args, g, b, st, ev);
-        if (inf && !outf) return launch_phased_t<true, false>(args, g, b, st, ev);
-        if (!inf && outf) return launch_phased_t<false, true>(args, g, b, st, ev);
-        return launch_phased_t<false, false>(args, g, b, st, ev);
+        if (inf && outf) return launch_phased_t<true, true>(args, wps, g, b, st, ev);
+        if (inf && !outf) return launch_phased_t<true, false>(args, wps, g, b, st, ev);
+        if (!inf && outf) return launch_phased_t<false, true>(args, wps, g, b, st, ev);
+        return launch_phased_t<false, false>(args, wps, g, b, st, ev);
     }
     args.phases = args.spp = 0;
     const int64_t block = t.reduce_block;

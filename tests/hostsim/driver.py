@@ -210,9 +210,12 @@ def main():
                     (17, 4000, 7), (33, 2049, 0), (64, 3001, 11), (5, 3, 0),
                     (5, 0, 0),
                     # the phased reduce (aligned slices of at least 8 steps per wave; the
-                    # stand-in device has 4 compute units = 32 waves x 52 steps x 256
+                    # stand-in device has 4 compute units = 16 waves x 104 steps x 256
                     # elements per phase): one phase, two phases, and the unaligned fallback
-                    (9, 270001, 0), (3, 600007, 0), (3, 600007, 1), (2, 66000, 4)]
+                    (9, 270001, 0), (3, 600007, 0), (3, 600007, 1), (2, 66000, 4),
+                    # full load groups: the one-wave-per-SIMD shape (104 steps held), one
+                    # phase and two (16 waves x 104 steps x 256 elements = 425 984 per phase)
+                    (8, 66003, 0), (16, 140001, 8), (8, 500009, 0)]
     for G, count, e0 in reduce_cases:
         for in_dt, out_dt in ((oracle.F32, oracle.F32), (oracle.F32, oracle.BF16),
                               (oracle.BF16, oracle.BF16), (oracle.BF16, oracle.F32)):

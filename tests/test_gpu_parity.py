@@ -279,14 +279,16 @@ def test_reduce_in_place_and_all_ranks():
 
 # The phased reduce (persistent waves that keep their sums in registers and
 # store them after their last load) only runs on aligned slices of at least 8
-# steps per wave (4.2 M fp32 / 8.4 M bf16 elements on 256 compute units), so
+# steps per wave (2.1 M fp32 / 4.2 M bf16 elements on 256 compute units), so
 # the small cases above never reach it.  Counts here sit just above that
 # threshold, with ragged tails (count % 4, a partial last step), every
 # remainder of G modulo the load group, and, for G = 2, more than one phase
 # (beyond 27.3 M elements).
 PHASED_CASES = [
     # G, count, elem_offset, in, out, knob
-    (1, 4194304, 0, oracle.F32, oracle.F32, 1),          # exactly 8 steps per wave
+    (1, 2097152, 0, oracle.F32, oracle.F32, 1),          # exactly 8 steps per wave
+    (1, 2097152 - 256, 0, oracle.F32, oracle.F32, 1),    # one step short: the other kernel
+    (6, 4194304, 0, oracle.F32, oracle.F32, 1),
     (2, 4194304 + 255, 0, oracle.F32, oracle.BF16, 1),   # partial last step, count % 4 = 3
     (3, 4300001, 4, oracle.F32, oracle.F32, 2),          # auto rule takes it (fp32 in and out, G >= 3)
     (5, 4200002, 8, oracle.F32, oracle.F32, 2),
@@ -294,7 +296,8 @@ PHASED_CASES = [
     (9, 4250000, 12, oracle.F32, oracle.BF16, 1),
     (12, 4200003, 0, oracle.F32, oracle.BF16, 2),        # auto rule takes every type pair from G = 12
     (15, 4194304 + 1, 0, oracle.F32, oracle.F32, 2),
-    (23, 4210000, 16, oracle.BF16, oracle.F32, 1),       # bf16 in needs 8.4 M elements: falls back
+    (23, 4210000, 16, oracle.BF16, oracle.F32, 1),       # bf16 in, just above its 4.2 M threshold
+    (4, 4100000, 8, oracle.BF16, oracle.BF16, 1),        # bf16 in, below it: the other kernel
     (16, 8388608 + 517, 8, oracle.BF16, oracle.BF16, 2), # bf16 in, 8 elements per lane and step
     (13, 8400007, 0, oracle.BF16, oracle.F32, 2),
     (7, 8388608 + 9, 16, oracle.BF16, oracle.BF16, 1),
@@ -323,6 +326,8 @@ def test_reduce_phased_parity(G, count, e0, in_dt, out_dt, knob):
     before = fcdp.fcdp_tuning_get("reduce_phased")
     try:
         fcdp.fcdp_tuning_set("reduce_phased", knob)
+        # the knob value 1 takes the shape the rule gives (one wave per SIMD for full
+        # load groups); G = 16 and 64 also run the two-wave shape below
         for scale in (None, float(np.float32(1.0 / G))):
             want = oracle.reduce(parts, e0, count, out_dt, scale)
             if scale is None:
@@ -339,6 +344,41 @@ def test_reduce_phased_parity(G, count, e0, in_dt, out_dt, knob):
     finally:
         fcdp.fcdp_tuning_set("reduce_phased", before)
     arena.check_guards()
+
+
+@pytest.mark.parametrize("G,in_dt,out_dt", [(8, oracle.F32, oracle.F32), (16, oracle.F32, oracle.BF16),
+                                            (24, oracle.BF16, oracle.BF16), (8, oracle.BF16, oracle.F32)])
+def test_reduce_phased_both_wave_shapes(G, in_dt, out_dt):
+    """The phased kernel is built in two shapes (one wave per SIMD holding 104
+    steps, two waves holding 52); with full load groups either can run: both
+    give the oracle's bits, over one phase and over two."""
+    for count in (2097152 + 64 * 4 * 5 + 3, 27262976 + 70003):
+        if in_dt == oracle.BF16:
+            count += 2097152                 # bf16 steps are 512 elements: stay above the threshold
+        g = synth.rng(0, 2900 + G, synth.KIND_GRAD, count % 1000)
+        parts = []
+        for r in range(G):
+            x = g.standard_normal(count, dtype=np.float32) * np.float32(1e-3)
+            parts.append(x if in_dt == oracle.F32 else synth.to_bf16_bits(x))
+        want = oracle.reduce(parts, 0, count, out_dt)
+        d_parts = [to_dev(p) for p in parts]
+        out = Arena([count * (4 if out_dt == oracle.F32 else 2)])
+        before = (fcdp.fcdp_tuning_get("reduce_phased"), fcdp.fcdp_tuning_get("reduce_phase_waves"))
+        try:
+            fcdp.fcdp_tuning_set("reduce_phased", 1)
+            for waves in (1, 2):
+                fcdp.fcdp_tuning_set("reduce_phase_waves", waves)
+                out.buf.fill_(0xC3)
+                fcdp.fcdp_reduce_grad_shard(d_parts, G, 0, count, in_dt, out_dt, out.ptr(0), None)
+                torch.cuda.synchronize()
+                _cmp_reduce(out.get(0, np.float32 if out_dt == oracle.F32 else np.uint16), want, out_dt)
+                out.check_guards()
+        finally:
+            fcdp.fcdp_tuning_set("reduce_phased", before[0])
+            fcdp.fcdp_tuning_set("reduce_phase_waves", before[1])
+        del d_parts
+        if G > 8:
+            break                            # the long case once is enough
 
 
 def test_reduce_phased_specials_in_place_and_both_kernels_agree():
