@@ -263,6 +263,7 @@ class Stack:
         r["k1_launches"], r["k1_ms"] = k1_n, k1_t / max(k1_n, 1)
         r["zc_launches"], r["zc_ms"] = zc_n, zc_t / max(zc_n, 1)
         r["k3_launches"], r["k3_ms"] = k3_n, k3_t / max(k3_n, 1)
+        r["k3_shape"] = fcdp.fcdp_tuning_get("last_reduce_shape")
         log("%s per step: forward %s ms, backward %s ms" % (
             self.cfg.name, " ".join("%.0f" % e0.elapsed_time(e1) for e0, e1, e2 in sweeps),
             " ".join("%.0f" % e1.elapsed_time(e2) for e0, e1, e2 in sweeps)))
@@ -744,7 +745,8 @@ def main():
                      "bytes_per_launch": head["k1_bytes"], "avg_launch_ms": round(head["k1_ms"], 4),
                      "launches_timed": head["k1_launches"]},
         "roofline_reduce": {"kernel": "%s (fp32 in, %s out)" % (
-                                "reduce_phased" if G >= 12 or (G >= 3 and out_f32) else "reduce_ranks",
+                                {0: "reduce_ranks", 1: "reduce_phased<104, 1, ...>", 2: "reduce_phased<52, 2, ...>"}[
+                                    head["k3_shape"]],
                                 "fp32" if out_f32 else "bf16"),
                             "bound": "hbm", "achieved": round(head["k3_gbps"], 1), "peak": HBM_PEAK_GBPS,
                             "unit": "GB/s", "frac": round(head["k3_gbps"] / HBM_PEAK_GBPS, 4),

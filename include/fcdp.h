@@ -461,7 +461,11 @@ const char *fcdp_last_error(void);
  *                         not lie inside a single allocation with at least
  *                         the documented number of bytes is FCDP_ESIZE
  *                         before anything is enqueued (no sizes cross this
- *                         boundary, so normal operation cannot check them). */
+ *                         boundary, so normal operation cannot check them).
+ * Read only (fcdp_tuning_set answers FCDP_EINVAL, as for an unknown name):
+ *   last_reduce_shape     what the last fcdp_reduce_grad_shard[_scaled] of the
+ *                         process launched: 0 one tile per workgroup, 1 or 2
+ *                         the phased kernel with that many waves per SIMD */
 fcdp_status fcdp_tuning_set(const char *name, int64_t value);
 int64_t fcdp_tuning_get(const char *name); /* -1 if unknown */
 

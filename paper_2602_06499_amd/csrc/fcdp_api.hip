@@ -1213,6 +1213,7 @@ int64_t fcdp_tuning_get(const char *name)
     if (n == "reduce_phased") return t.reduce_phased;
     if (n == "reduce_phase_waves") return t.reduce_phase_waves;
     if (n == "debug_poison") return t.debug_poison;
+    if (n == "last_reduce_shape") return fcdp::last_reduce_shape();
     return -1;
 }
 

@@ -172,6 +172,9 @@ int launch_plain_copy(void *dst, const void *src, size_t bytes, void *stream,
 // dst 16-byte aligned, bytes even; max_wgs 0 = up to 16384 workgroups
 int launch_fill(void *dst, size_t bytes, uint16_t pattern, void *stream, int64_t max_wgs = 0);
 int device_cu_count();
+// What the last launch_reduce of the process used: 0 one tile per workgroup,
+// 1 or 2 the phased kernel with that many waves per SIMD.
+int last_reduce_shape();
 
 } // namespace fcdp
 #endif

@@ -518,41 +518,20 @@ __device__ __forceinline__ void widen_unit(const u32x4 r, float (&v)[IN_F32 ? 4 
     }
 }
 
-// Stores one lane's E finished sums: E * 4 bytes (fp32) or E * 2 bytes (bf16).
-// Plain stores: with all stores of the chip in one burst they measured 1-2 %
-// faster than non-temporal ones.
-template <bool OUT_F32, int E>
-__device__ __forceinline__ void store_unit(char *out, int64_t unit, const float (&a)[E])
+// The loads of partials g0 .. g0+K-1 of one unit, issued back to back.
+template <int K, bool NT>
+__device__ __forceinline__ void issue_group(const ReduceArgs &a, int g0, int64_t unit,
+                                            u32x4 (&r)[K])
 {
-    if constexpr (OUT_F32) {
-#pragma unroll
-        for (int h = 0; h < E / 4; ++h)
-            store16<false>(out + unit * (E * 4) + h * 16,
-                           u32x4{__float_as_uint(a[4 * h]), __float_as_uint(a[4 * h + 1]),
-                                 __float_as_uint(a[4 * h + 2]), __float_as_uint(a[4 * h + 3])});
-    } else if constexpr (E == 8) {
-        store16<false>(out + unit * 16,
-                       u32x4{bf16_rne_bits(a[0]) | (bf16_rne_bits(a[1]) << 16),
-                             bf16_rne_bits(a[2]) | (bf16_rne_bits(a[3]) << 16),
-                             bf16_rne_bits(a[4]) | (bf16_rne_bits(a[5]) << 16),
-                             bf16_rne_bits(a[6]) | (bf16_rne_bits(a[7]) << 16)});
-    } else {
-        *reinterpret_cast<u32x2 *>(out + unit * 8) =
-            u32x2{bf16_rne_bits(a[0]) | (bf16_rne_bits(a[1]) << 16),
-                  bf16_rne_bits(a[2]) | (bf16_rne_bits(a[3]) << 16)};
-    }
-}
-
-// Adds partials g0 .. g0+K-1 of one unit to acc in that order; the K loads
-// are issued before the first add.
-template <int K, bool IN_F32, bool NT>
-__device__ __forceinline__ void add_group1(const ReduceArgs &a, int g0, int64_t unit,
-                                           float (&acc)[IN_F32 ? 4 : 8])
-{
-    constexpr int E = IN_F32 ? 4 : 8;
-    u32x4 r[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) r[k] = load16<16, NT>(a.p[g0 + k] + unit * 16);
+}
+
+// Adds the K loaded partials to acc in their order.
+template <int K, bool IN_F32>
+__device__ __forceinline__ void consume_group(const u32x4 (&r)[K], float (&acc)[IN_F32 ? 4 : 8])
+{
+    constexpr int E = IN_F32 ? 4 : 8;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         float v[E];
@@ -562,17 +541,90 @@ __device__ __forceinline__ void add_group1(const ReduceArgs &a, int g0, int64_t 
     }
 }
 
+// Adds partials g0 .. g0+K-1 of one unit to acc in that order; the K loads
+// are issued before the first add.
+template <int K, bool IN_F32, bool NT>
+__device__ __forceinline__ void add_group1(const ReduceArgs &a, int g0, int64_t unit,
+                                           float (&acc)[IN_F32 ? 4 : 8])
+{
+    u32x4 r[K];
+    issue_group<K, NT>(a, g0, unit, r);
+    consume_group<K, IN_F32>(r, acc);
+}
+
+// What a lane holds of a step until the phase's stores.  For fp32 output
+// these are the sums themselves, added up in place and scaled at the store.
+// For bf16 output they are the scaled sums already rounded, two to a word:
+// half the registers, and the rounding arithmetic is done while loads are in
+// flight instead of in front of the stores.
+template <bool OUT_F32, int E>
+struct HeldUnit;
+template <int E>
+struct HeldUnit<true, E> {
+    float f[E];
+};
+template <int E>
+struct HeldUnit<false, E> {
+    uint32_t w[E / 2];
+};
+
+// Where the sums of the step in progress are added up: in place for fp32
+// output, in a temporary for bf16 output.
+template <int E>
+__device__ __forceinline__ float (&sums_of(HeldUnit<true, E> &h, float (&)[E]))[E] { return h.f; }
+template <int E>
+__device__ __forceinline__ float (&sums_of(HeldUnit<false, E> &, float (&t)[E]))[E] { return t; }
+
+// A finished step's sums into their held form (nothing to do for fp32).
+template <int E>
+__device__ __forceinline__ void finish_unit(const float (&)[E], float, HeldUnit<true, E> &) {}
+template <int E>
+__device__ __forceinline__ void finish_unit(const float (&t)[E], float scale, HeldUnit<false, E> &h)
+{
+#pragma unroll
+    for (int c = 0; c < E / 2; ++c)
+        h.w[c] = bf16_rne_bits(t[2 * c] * scale) | (bf16_rne_bits(t[2 * c + 1] * scale) << 16);
+}
+
+// Plain stores: with all stores of the chip in one burst they measured 1-2 %
+// faster than non-temporal ones.
+template <int E>
+__device__ __forceinline__ void store_held(char *out, int64_t unit, float scale,
+                                           const HeldUnit<true, E> &h)
+{
+#pragma unroll
+    for (int q = 0; q < E / 4; ++q)
+        store16<false>(out + unit * (E * 4) + q * 16,
+                       u32x4{__float_as_uint(h.f[4 * q] * scale), __float_as_uint(h.f[4 * q + 1] * scale),
+                             __float_as_uint(h.f[4 * q + 2] * scale),
+                             __float_as_uint(h.f[4 * q + 3] * scale)});
+}
+template <int E>
+__device__ __forceinline__ void store_held(char *out, int64_t unit, float,
+                                           const HeldUnit<false, E> &h)
+{
+    if constexpr (E == 4)
+        *reinterpret_cast<u32x2 *>(out + unit * 8) = u32x2{h.w[0], h.w[1]};
+    else
+        store16<false>(out + unit * 16, u32x4{h.w[0], h.w[1], h.w[2], h.w[3]});
+}
+
 // Needs 16-byte aligned input slices and output (the launcher falls back to
 // reduce_ranks otherwise).  A unit is 16 bytes of input = E elements; a step
 // is 64 units, one per lane; a wave holds up to STEPS = STEPS4 * 4 / E
-// steps, i.e. STEPS4 * 4 sums per lane whatever the input type.  WPE = waves
-// per SIMD the register budget is cut for (1: 512 registers, 2: 256).
+// steps, i.e. at most STEPS4 * 4 words per lane whatever the types.  WPE =
+// waves per SIMD the register budget is cut for (1: 512 registers, 2: 256).
+// For bf16 output a step's sums are scaled and rounded while the first loads
+// of the next step are in flight, so that this arithmetic, like the adds,
+// runs under memory latency and only the stores are left for the end (at one
+// wave per SIMD and G = 8 that alone is 0.73 -> 0.83 of the HBM peak).
 template <int STEPS4, int WPE, int REM, bool IN_F32, bool OUT_F32, bool NT>
 __global__ void __launch_bounds__(kPhasedBlock, WPE) // threads, waves per SIMD
 reduce_phased(const ReduceArgs a)
 {
     constexpr int E = IN_F32 ? 4 : 8;
     constexpr int STEPS = STEPS4 * 4 / E;
+    constexpr int K0 = REM > 0 ? REM : kPhasedGroup; // the first group when no group is full
     const int64_t n_units = a.count / E;
     const int64_t n_steps = (n_units + 63) >> 6;
     const int64_t w = static_cast<int64_t>(blockIdx.x) * (kPhasedBlock / 64) +
@@ -582,19 +634,46 @@ reduce_phased(const ReduceArgs a)
     for (int p = 0; p < a.phases; ++p) {
         // this wave's run of the phase: steps [s0, s0 + spp)
         const int64_t s0 = (w * a.phases + p) * a.spp;
-        float acc[STEPS][E];
+        HeldUnit<OUT_F32, E> held[STEPS];
+        float tmp[2][E]; // bf16 output: the sums of the step in progress and of the one before it
 #pragma unroll
-        for (int j = 0; j < STEPS; ++j) {
+        for (int j = 0; j <= STEPS; ++j) {
             const int64_t s = s0 + j;
-            if (j < a.spp && s < n_steps) { // the same for every lane of the wave
+            // the same for every lane of the wave; an active step follows active steps only
+            const bool active = j < STEPS && j < a.spp && s < n_steps;
+            const bool prev_active = j > 0 && (j - 1) < a.spp && (s - 1) < n_steps;
+            if (active) {
                 const int64_t idx = (s << 6) + lane;
                 // the last step may be partial: clamp the load index, skip the store
                 const int64_t lidx = idx < n_units ? idx : n_units - 1;
+                float (&cur)[E] = sums_of<E>(held[j < STEPS ? j : 0], tmp[j & 1]);
+                if constexpr (OUT_F32) {
 #pragma unroll
-                for (int c = 0; c < E; ++c) acc[j][c] = -0.0f; // the identity of IEEE addition, also for -0
-                for (int g = 0; g < full; g += kPhasedGroup)
-                    add_group1<kPhasedGroup, IN_F32, NT>(a, g, lidx, acc[j]);
-                if constexpr (REM > 0) add_group1<REM, IN_F32, NT>(a, full, lidx, acc[j]);
+                    for (int c = 0; c < E; ++c) cur[c] = -0.0f; // the identity of IEEE addition, also for -0
+                    for (int g = 0; g < full; g += kPhasedGroup)
+                        add_group1<kPhasedGroup, IN_F32, NT>(a, g, lidx, cur);
+                    if constexpr (REM > 0) add_group1<REM, IN_F32, NT>(a, full, lidx, cur);
+                } else if (REM == 0 || full > 0) {
+                    // the step before is rounded between the first loads of this one and their adds
+                    u32x4 r[kPhasedGroup];
+                    issue_group<kPhasedGroup, NT>(a, 0, lidx, r);
+                    if (j > 0) finish_unit<E>(tmp[(j - 1) & 1], a.scale, held[j > 0 ? j - 1 : 0]);
+#pragma unroll
+                    for (int c = 0; c < E; ++c) cur[c] = -0.0f;
+                    consume_group<kPhasedGroup, IN_F32>(r, cur);
+                    for (int g = kPhasedGroup; g < full; g += kPhasedGroup)
+                        add_group1<kPhasedGroup, IN_F32, NT>(a, g, lidx, cur);
+                    if constexpr (REM > 0) add_group1<REM, IN_F32, NT>(a, full, lidx, cur);
+                } else {
+                    u32x4 r[K0];
+                    issue_group<K0, NT>(a, 0, lidx, r);
+                    if (j > 0) finish_unit<E>(tmp[(j - 1) & 1], a.scale, held[j > 0 ? j - 1 : 0]);
+#pragma unroll
+                    for (int c = 0; c < E; ++c) cur[c] = -0.0f;
+                    consume_group<K0, IN_F32>(r, cur);
+                }
+            } else if (prev_active) {
+                finish_unit<E>(tmp[(j - 1) & 1], a.scale, held[j > 0 ? j - 1 : 0]);
             }
         }
 #pragma unroll
@@ -602,9 +681,7 @@ reduce_phased(const ReduceArgs a)
             const int64_t s = s0 + j;
             if (j < a.spp && s < n_steps) {
                 const int64_t idx = (s << 6) + lane;
-#pragma unroll
-                for (int c = 0; c < E; ++c) acc[j][c] = acc[j][c] * a.scale;
-                if (idx < n_units) store_unit<OUT_F32, E>(a.out, idx, acc[j]);
+                if (idx < n_units) store_held<E>(a.out, idx, a.scale, held[j]);
             }
         }
     }
@@ -737,6 +814,7 @@ __global__ void __launch_bounds__(256) reduce_runs(const ReduceRunArgs a)
 }
 
 std::atomic<int> g_cu_count[kMaxDevices]; // 0 = not asked yet; any thread may fill it in
+std::atomic<int> g_last_reduce_shape{0};  // what the last launch_reduce of the process picked
 
 // Launches `kernel`; with timing events the dispatch itself carries them.
 template <typename K, typename A>
@@ -828,6 +906,8 @@ hipError_t launch_reduce_t(const ReduceArgs &args, dim3 grid, dim3 block, hipStr
 }
 
 } // namespace
+
+int last_reduce_shape() { return g_last_reduce_shape.load(std::memory_order_relaxed); }
 
 int device_cu_count()
 {
@@ -1004,14 +1084,16 @@ int launch_reduce(const void *const *partials, int32_t G, int64_t elem_offset,
     const int64_t nvec = count >> 2;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool inf = in_dtype == FCDP_F32, outf = out_dtype == FCDP_F32;
-    // the persistent grid: every wave resident at once.  Where each kernel pays (30
+    // the persistent grid: every wave resident at once.  Where each kernel pays (20
     // launches each on MI355X, a 25 M-element shard, G = 1..64, all four type pairs,
     // fractions of the HBM peak): with G a multiple of 8 the one-wave-per-SIMD shape
-    // beats one tile per workgroup for an fp32 shard from G = 8 on (0.86 against 0.78
-    // at G = 8, 16 and 32) and for a bf16 shard from G = 16 on (0.82-0.84 against
-    // 0.81); otherwise the two-wave shape does for fp32 partials into an fp32 shard
-    // from G = 3 on (+1 to +9 points) and for every other type pair from G = 12 on
-    // (+1 to +5); below that one tile per workgroup is 1-4 points faster.
+    // is the fastest from G = 8 on (0.83-0.86 against 0.75-0.81 for one tile per
+    // workgroup), bf16 partials into a bf16 shard at G = 8 aside (two waves 0.78,
+    // one 0.77).  For other G the two-wave shape wins from G = 3 on when both types
+    // are equal (fp32 0.80-0.83 against 0.77-0.80, bf16 0.78-0.82 against 0.72-0.76),
+    // from G = 5 on for fp32 partials into a bf16 shard (0.81-0.84 against 0.78-0.81)
+    // and from G = 12 on for bf16 partials into an fp32 shard; below that one tile
+    // per workgroup is faster (at G = 1 by 0.78 against 0.51).
     const int64_t wpb = kPhasedBlock / 64;
     const int64_t epu = inf ? 4 : 8;                       // elements per 16-byte unit
     const int64_t n_steps = (count / epu + 63) / 64;
@@ -1019,11 +1101,12 @@ int launch_reduce(const void *const *partials, int32_t G, int64_t elem_offset,
     if (t.reduce_phased == 1) {
         wps = t.reduce_phase_waves ? static_cast<int>(t.reduce_phase_waves) : (G % kPhasedGroup == 0 ? 1 : 2);
     } else if (t.reduce_phased == 2) {
-        if (G % kPhasedGroup == 0 && (outf ? G >= 8 : G >= 16)) wps = 1;
-        else if (G % kPhasedGroup != 0 && (G >= 12 || (G >= 3 && inf && outf))) wps = 2;
+        if (G % kPhasedGroup == 0) wps = (G == 8 && !inf && !outf) ? 2 : 1;
+        else if (G >= 12 || (G >= 3 && inf == outf) || (G >= 5 && inf && !outf)) wps = 2;
         if (wps && t.reduce_phase_waves) wps = static_cast<int>(t.reduce_phase_waves);
     }
     if (wps == 1 && G % kPhasedGroup != 0) wps = 2;        // the one-wave shape is built for full groups only
+    g_last_reduce_shape.store(0, std::memory_order_relaxed);
     const int64_t W = static_cast<int64_t>(device_cu_count()) * 4 * (wps ? wps : 1);
     if (wps && aligned && (reinterpret_cast<uintptr_t>(out) & 15u) == 0 &&
         n_steps >= W * kPhasedMinStepsPerWave) {
@@ -1033,6 +1116,7 @@ int launch_reduce(const void *const *partials, int32_t G, int64_t elem_offset,
         args.phases = static_cast<int32_t>(phases);
         args.spp = static_cast<int32_t>((n_steps + W * phases - 1) / (W * phases)); // <= steps_cap
         const dim3 g(static_cast<unsigned>(W / wpb)), b(kPhasedBlock);
+        g_last_reduce_shape.store(wps, std::memory_order_relaxed);
         if (inf && outf) return launch_phased_t<true, true>(args, wps, g, b, st, ev);
         if (inf && !outf) return launch_phased_t<true, false>(args, wps, g, b, st, ev);
         if (!inf && outf) return launch_phased_t<false, true>(args, wps, g, b, st, ev);

@@ -352,9 +352,9 @@ def test_reduce_phased_both_wave_shapes(G, in_dt, out_dt):
     """The phased kernel is built in two shapes (one wave per SIMD holding 104
     steps, two waves holding 52); with full load groups either can run: both
     give the oracle's bits, over one phase and over two."""
-    for count in (2097152 + 64 * 4 * 5 + 3, 27262976 + 70003):
-        if in_dt == oracle.BF16:
-            count += 2097152                 # bf16 steps are 512 elements: stay above the threshold
+    for count in (4194304 + 64 * 4 * 5 + 3, 27262976 + 70003):
+        if in_dt == oracle.BF16 and count < 8388608:
+            count *= 2                       # bf16 steps are 512 elements: stay above the two-wave threshold
         g = synth.rng(0, 2900 + G, synth.KIND_GRAD, count % 1000)
         parts = []
         for r in range(G):
@@ -371,6 +371,7 @@ def test_reduce_phased_both_wave_shapes(G, in_dt, out_dt):
                 out.buf.fill_(0xC3)
                 fcdp.fcdp_reduce_grad_shard(d_parts, G, 0, count, in_dt, out_dt, out.ptr(0), None)
                 torch.cuda.synchronize()
+                assert fcdp.fcdp_tuning_get("last_reduce_shape") == waves   # the shape asked for did run
                 _cmp_reduce(out.get(0, np.float32 if out_dt == oracle.F32 else np.uint16), want, out_dt)
                 out.check_guards()
         finally:
@@ -379,6 +380,35 @@ def test_reduce_phased_both_wave_shapes(G, in_dt, out_dt):
         del d_parts
         if G > 8:
             break                            # the long case once is enough
+
+
+RULE_CASES = [  # G, in, out -> waves per SIMD of the phased kernel, 0 = one tile per workgroup
+    (1, oracle.F32, oracle.F32, 0), (2, oracle.BF16, oracle.BF16, 0),
+    (3, oracle.F32, oracle.F32, 2), (3, oracle.BF16, oracle.BF16, 2), (3, oracle.F32, oracle.BF16, 0),
+    (4, oracle.BF16, oracle.F32, 0), (5, oracle.F32, oracle.BF16, 2), (6, oracle.BF16, oracle.F32, 0),
+    (8, oracle.F32, oracle.F32, 1), (8, oracle.F32, oracle.BF16, 1), (8, oracle.BF16, oracle.F32, 1),
+    (8, oracle.BF16, oracle.BF16, 2), (12, oracle.BF16, oracle.F32, 2),
+    (16, oracle.BF16, oracle.BF16, 1), (16, oracle.F32, oracle.BF16, 1),
+]
+
+
+@pytest.mark.parametrize("G,in_dt,out_dt,shape", RULE_CASES)
+def test_reduce_rule_picks_the_documented_shape(G, in_dt, out_dt, shape):
+    """Left to its rule (the default), the reduce launches the kernel shape the
+    header documents for this rank count and type pair; an input too short
+    for the persistent grid takes one tile per workgroup whatever the rule."""
+    assert fcdp.fcdp_tuning_get("reduce_phased") == 2 and fcdp.fcdp_tuning_get("reduce_phase_waves") == 0
+    ies = 4 if in_dt == oracle.F32 else 2
+    count = 4300000 * (4 // ies)
+    buf = torch.zeros(count * ies, dtype=torch.uint8, device="cuda")   # every rank reads the same zeros
+    out = torch.empty(count * 4, dtype=torch.uint8, device="cuda")
+    ptrs = [buf.data_ptr()] * G
+    fcdp.fcdp_reduce_grad_shard(ptrs, G, 0, count, in_dt, out_dt, out.data_ptr(), None)
+    torch.cuda.synchronize()
+    assert fcdp.fcdp_tuning_get("last_reduce_shape") == shape
+    fcdp.fcdp_reduce_grad_shard(ptrs, G, 0, 100000, in_dt, out_dt, out.data_ptr(), None)
+    torch.cuda.synchronize()
+    assert fcdp.fcdp_tuning_get("last_reduce_shape") == 0
 
 
 def test_reduce_phased_specials_in_place_and_both_kernels_agree():
