@@ -48,9 +48,9 @@ LINK_PEAK_GBPS = 63.0           # PCIe Gen5 x16 per direction, 128b/130b
 TRAFFIC_SOURCE = "profiles/unflatten_reduce_hbm_traffic.md"
 MEASURED_TRAFFIC = {
     # config: (unflatten, reduce fp32 out, reduce bf16 out) in bytes per launch
-    "llama7b_g8": (822.2e6, 911.3e6, 860.2e6),
-    "llama13b_g16": (1288.7e6, 1348.7e6, 1309.2e6),
-    "llama70b_g32": (3476.1e6, 3530.1e6, 3476.9e6),
+    "llama7b_g8": (822.2e6, 912.4e6, 862.6e6),
+    "llama13b_g16": (1288.7e6, 1349.8e6, 1310.9e6),
+    "llama70b_g32": (3476.1e6, 3531.3e6, 3478.7e6),
 }
 
 
@@ -90,8 +90,12 @@ def parse():
                     help="size of the host-link probe copy (16: the transfer size of the paper's Table 3, first row)")
     ap.add_argument("--reduce-study", action="store_true",
                     help="instead of the benchmark: the gradient-shard reduce at the 7B / 13B / 70B shard sizes "
-                         "(G = 8, 16, 32) with both kernels, next to the G:1 calibration stream and a read-only "
-                         "pass; prints one JSON line")
+                         "(G = 8, 16, 32) with both kernels, next to the G:1 calibration stream; "
+                         "prints one JSON line")
+    ap.add_argument("--reduce-sweep", action="store_true",
+                    help="instead of the benchmark: the reduce kernels over G = 1..64 and the four type pairs at a "
+                         "25 M-element shard (one tile per workgroup, phased at one and at two waves per SIMD, "
+                         "and the default rule's pick); prints one JSON line")
     return ap.parse_args()
 
 
@@ -363,6 +367,52 @@ def reduce_study(fcdp, synth, torch):
                       "rows": rows}), flush=True)
 
 
+def reduce_sweep(fcdp, torch, S=25297920):
+    """The measurement behind the library's choice of reduce kernel: for a
+    range of G and the four type pairs, kernel-only fractions of the HBM peak
+    of one tile per workgroup, of the phased kernel at one and at two waves
+    per SIMD, and of what the default rule picks."""
+    dev = torch.device("cuda:0")
+    st = torch.cuda.Stream()
+    before = (fcdp.fcdp_tuning_get("reduce_phased"), fcdp.fcdp_tuning_get("reduce_phase_waves"))
+    rows = []
+    try:
+        for G in (1, 2, 3, 4, 6, 8, 9, 10, 12, 14, 16, 20, 24, 32, 40, 64):
+            NB = 3
+            ps = [torch.empty(G, S, dtype=torch.float32, device=dev).normal_(0, 1e-3) for _ in range(NB)]
+            ptrs = [fcdp.pointer_array([p.data_ptr() + r * S * 4 for r in range(G)]) for p in ps]
+            outs = [torch.empty(S, dtype=torch.float32, device=dev) for _ in range(NB)]
+            for idt, iname, isz in ((fcdp.F32, "fp32", 4), (fcdp.BF16, "bf16", 2)):
+                for odt, oname, osz in ((fcdp.F32, "fp32", 4), (fcdp.BF16, "bf16", 2)):
+                    row = {"G": G, "in": iname, "out": oname}
+                    for name, phased, waves in (("tiles", 0, 0), ("one", 1, 1), ("two", 1, 2), ("rule", 2, 0)):
+                        if waves == 1 and G % 8:
+                            continue                  # the one-wave shape is built for full load groups
+                        fcdp.fcdp_tuning_set("reduce_phased", phased)
+                        fcdp.fcdp_tuning_set("reduce_phase_waves", waves)
+                        reps = 20
+                        for i in range(3):
+                            fcdp.fcdp_reduce_grad_shard(ptrs[i % NB], G, 0, S, idt, odt, outs[i % NB], st)
+                        torch.cuda.synchronize()
+                        fcdp.fcdp_timing_enable(reps + 4)
+                        for i in range(reps):
+                            fcdp.fcdp_reduce_grad_shard(ptrs[i % NB], G, 0, S, idt, odt, outs[i % NB], st)
+                        torch.cuda.synchronize()
+                        n, ms = fcdp.fcdp_timing_collect(fcdp.KERNEL_REDUCE)
+                        fcdp.fcdp_timing_enable(0)
+                        row[name] = round((G * S * isz + S * osz) / (ms / n * 1e-3) / 1e9 / HBM_PEAK_GBPS, 3)
+                        if name == "rule":
+                            row["rule_shape"] = fcdp.fcdp_tuning_get("last_reduce_shape")
+                    rows.append(row)
+                    log("G=%d %s -> %s: %s" % (G, iname, oname, {k: v for k, v in row.items() if k not in ("G", "in", "out")}))
+            del ps, outs
+    finally:
+        fcdp.fcdp_tuning_set("reduce_phased", before[0])
+        fcdp.fcdp_tuning_set("reduce_phase_waves", before[1])
+    print(json.dumps({"study": "reduce kernels over G and type pairs, fractions of the HBM peak", "S": S,
+                      "peak_gbps": HBM_PEAK_GBPS, "rows": rows}), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -379,6 +429,9 @@ def main():
     dev = torch.device("cuda:0")
     if args.reduce_study:
         reduce_study(fcdp, synth, torch)
+        return
+    if args.reduce_sweep:
+        reduce_sweep(fcdp, torch)
         return
     host = host_info()
     if args.copies_in_flight >= 0:

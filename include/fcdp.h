@@ -435,7 +435,12 @@ const char *fcdp_last_error(void);
  *                         that the chip reads, then writes) whenever slices
  *                         and output are 16-byte aligned and at least 8 steps
  *                         per wave long; 2 the phased kernel where it measured
- *                         faster, by G and the two element types (2).
+ *                         faster (2): G a multiple of 8 takes it at one wave
+ *                         per SIMD (bf16 partials into a bf16 shard at G = 8:
+ *                         two); other G take it at two waves per SIMD from
+ *                         G = 3 on when partials and shard have one type, from
+ *                         G = 5 on for fp32 partials into a bf16 shard, from
+ *                         G = 12 on for bf16 partials into an fp32 shard.
  *                         The result is the same bits either way.
  *   reduce_phase_waves    waves per SIMD of the phased kernel: 1 (104 steps
  *                         held per wave; built for G a multiple of 8 only,
