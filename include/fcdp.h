@@ -440,11 +440,22 @@ const char *fcdp_last_error(void);
  *                         two); other G take it at two waves per SIMD from
  *                         G = 3 on when partials and shard have one type, from
  *                         G = 5 on for fp32 partials into a bf16 shard, from
- *                         G = 12 on for bf16 partials into an fp32 shard.
+ *                         G = 12 on for bf16 partials into an fp32 shard; and
+ *                         by length: an input beyond what one launch holds
+ *                         (waves x held steps: 27.26 M elements on a 256-CU
+ *                         part) takes full launches and then the rest; a
+ *                         launch filled below 0.7 of that takes two waves
+ *                         per SIMD if G >= 12, else one tile per workgroup,
+ *                         as does any launch filled below 0.46.
  *                         The result is the same bits either way.
  *   reduce_phase_waves    waves per SIMD of the phased kernel: 1 (104 steps
  *                         held per wave; built for G a multiple of 8 only,
  *                         other G take 2), 2 (52 steps), 0 by rule (0)
+ *   reduce_phase_rotate   where a wave of the phased kernel starts its run
+ *                         of steps: 0 at the first step, 2 at step
+ *                         (wave index mod run length), wrapping around,
+ *                         1 the second only for the run lengths at which
+ *                         the first measured slow (1)
  *   link_max_wgs          workgroups of the zero-copy fetch / store kernels,
  *                         0 = no bound (64)
  *   link_block            their threads per workgroup (256)

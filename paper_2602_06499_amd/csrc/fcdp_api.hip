@@ -1181,6 +1181,9 @@ try {
     } else if (n == "reduce_phased") {
         if (v < 0 || v > 2) return fail(FCDP_EINVAL, "reduce_phased: 0, 1 or 2");
         t.reduce_phased = v;
+    } else if (n == "reduce_phase_rotate") {
+        if (v < 0 || v > 2) return fail(FCDP_EINVAL, "reduce_phase_rotate: 0, 1 or 2");
+        t.reduce_phase_rotate = v;
     } else if (n == "reduce_phase_waves") {
         if (v < 0 || v > 2) return fail(FCDP_EINVAL, "reduce_phase_waves: 0, 1 or 2");
         t.reduce_phase_waves = v;
@@ -1212,6 +1215,7 @@ int64_t fcdp_tuning_get(const char *name)
     if (n == "reduce_block") return t.reduce_block;
     if (n == "reduce_phased") return t.reduce_phased;
     if (n == "reduce_phase_waves") return t.reduce_phase_waves;
+    if (n == "reduce_phase_rotate") return t.reduce_phase_rotate;
     if (n == "debug_poison") return t.debug_poison;
     if (n == "last_reduce_shape") return fcdp::last_reduce_shape();
     return -1;

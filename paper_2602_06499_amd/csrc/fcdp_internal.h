@@ -107,6 +107,7 @@ struct Tuning {
     // waves per SIMD of the phased kernel: 0 by rule (one when every load group
     // is full, two otherwise), 1 or 2 forced (1 falls back to 2 for other G)
     int64_t reduce_phase_waves = 0;
+    int64_t reduce_phase_rotate = 1;
     // debugging aid, off by default (the environment variable FCDP_DEBUG_POISON=1
     // turns it on at load): outputs are filled with kPoison before the work that
     // writes them is enqueued, so a consumer that misses a wait reads poison

@@ -243,9 +243,8 @@ struct ReduceArgs {
     int64_t count;
     int32_t G;
     float scale; // multiplies the finished sum; 1.0f leaves every value as it is
-    // reduce_phased only: a wave runs `phases` phases of at most `spp` steps
-    int32_t phases;
-    int32_t spp;
+    int32_t spp;    // phased kernel: steps per wave
+    int32_t rotate; // phased kernel: start each full run at step w mod spp
 };
 
 __device__ __forceinline__ uint32_t bf16_rne_bits(float x)
@@ -472,9 +471,9 @@ __global__ void __launch_bounds__(64) reduce_stream_calibration(const StreamArgs
 // registers that the compiler uses as backing store) and stores them only
 // after its last load of the phase.  All waves have the same work, so they
 // reach their stores at about the same time and the stores arrive at the
-// memory as one burst.  With 104 steps one phase holds 1024 waves x
+// memory as one burst.  With 104 steps one launch holds 1024 waves x
 // 104 KiB = 109 MB of fp32 sums on a 256-CU part, i.e. the whole shard of
-// every Llama-shaped layer here; longer inputs take several phases.  Fewer,
+// every Llama-shaped layer here; longer inputs take several launches.  Fewer,
 // fatter waves measured faster at every step of the way (G = 32, fp32 out,
 // fraction of the HBM peak): 16 steps at four waves per SIMD 0.80, 24 at
 // three 0.83, 48 at two 0.85, 96 at one 0.87; so did a contiguous run per
@@ -631,17 +630,23 @@ reduce_phased(const ReduceArgs a)
                       __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
     const int lane = static_cast<int>(threadIdx.x & 63u);
     const int full = a.G - REM; // REM = G mod kPhasedGroup
-    for (int p = 0; p < a.phases; ++p) {
-        // this wave's run of the phase: steps [s0, s0 + spp)
-        const int64_t s0 = (w * a.phases + p) * a.spp;
+    {
+        // this wave's run: steps [s0, s0 + spp)
+        const int64_t s0 = w * a.spp;
+        // A wave whose whole run exists may start it at step w mod spp and wrap around
+        // (the launcher asks for that where equal positions in every run would make the
+        // chip read a comb of addresses that the memory maps badly).
+        const int rot = (a.rotate && s0 + a.spp <= n_steps)
+                            ? static_cast<int>(static_cast<uint32_t>(w) % static_cast<uint32_t>(a.spp)) : 0;
         HeldUnit<OUT_F32, E> held[STEPS];
         float tmp[2][E]; // bf16 output: the sums of the step in progress and of the one before it
 #pragma unroll
         for (int j = 0; j <= STEPS; ++j) {
-            const int64_t s = s0 + j;
+            const int64_t s = s0 + (j + rot < a.spp ? j + rot : j + rot - a.spp);
             // the same for every lane of the wave; an active step follows active steps only
+            // (a rotated run is active throughout)
             const bool active = j < STEPS && j < a.spp && s < n_steps;
-            const bool prev_active = j > 0 && (j - 1) < a.spp && (s - 1) < n_steps;
+            const bool prev_active = j > 0 && (j - 1) < a.spp && (rot != 0 || s0 + j - 1 < n_steps);
             if (active) {
                 const int64_t idx = (s << 6) + lane;
                 // the last step may be partial: clamp the load index, skip the store
@@ -678,7 +683,7 @@ reduce_phased(const ReduceArgs a)
         }
 #pragma unroll
         for (int j = 0; j < STEPS; ++j) {
-            const int64_t s = s0 + j;
+            const int64_t s = s0 + (j + rot < a.spp ? j + rot : j + rot - a.spp);
             if (j < a.spp && s < n_steps) {
                 const int64_t idx = (s << 6) + lane;
                 if (idx < n_units) store_held<E>(a.out, idx, a.scale, held[j]);
@@ -820,7 +825,7 @@ std::atomic<int> g_last_reduce_shape{0};  // what the last launch_reduce of the 
 template <typename K, typename A>
 hipError_t launch_one(K kernel, dim3 grid, dim3 block, hipStream_t st, const LaunchEvents &ev, const A &args)
 {
-    if (ev.start && ev.stop)
+    if (ev.start || ev.stop) // either may be null: a call of several dispatches starts on its first, stops on its last
         hipExtLaunchKernelGGL(kernel, grid, block, 0, st, static_cast<hipEvent_t>(ev.start),
                               static_cast<hipEvent_t>(ev.stop), 0, args);
     else
@@ -1081,11 +1086,10 @@ int launch_reduce(const void *const *partials, int32_t G, int64_t elem_offset,
     args.G = G;
     args.scale = scale;
     const Tuning &t = tuning();
-    const int64_t nvec = count >> 2;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool inf = in_dtype == FCDP_F32, outf = out_dtype == FCDP_F32;
-    // the persistent grid: every wave resident at once.  Where each kernel pays (20
-    // launches each on MI355X, a 25 M-element shard, G = 1..64, all four type pairs,
+    // The persistent grid: every wave resident at once.  Where each kernel pays by G
+    // and type pair (20 launches each on MI355X, a 25 M-element shard, G = 1..64,
     // fractions of the HBM peak): with G a multiple of 8 the one-wave-per-SIMD shape
     // is the fastest from G = 8 on (0.83-0.86 against 0.75-0.81 for one tile per
     // workgroup), bf16 partials into a bf16 shard at G = 8 aside (two waves 0.78,
@@ -1094,50 +1098,102 @@ int launch_reduce(const void *const *partials, int32_t G, int64_t elem_offset,
     // from G = 5 on for fp32 partials into a bf16 shard (0.81-0.84 against 0.78-0.81)
     // and from G = 12 on for bf16 partials into an fp32 shard; below that one tile
     // per workgroup is faster (at G = 1 by 0.78 against 0.51).
+    // And by length: a launch has a fixed cost (the ramp, the tail, the store burst),
+    // so a phased launch must be long.  One launch holds C = waves x held steps.  A
+    // longer input takes full launches of C steps and then what is left (the kernel
+    // boundary keeps one launch's stores out of the next one's reads: 0.80 of the
+    // peak at 200 M elements, against 0.66 with the passes inside one kernel and 0.73
+    // for one tile per workgroup).  What a launch of fewer than C steps runs: the
+    // one-wave shape from 0.7 C on (below that it falls behind the others: at half
+    // of C 0.76 against 0.80 at G = 8); the two-wave shape from 0.46 C on, for G = 8
+    // only where it is the rule's pick anyway (at G = 8 it merely ties with one tile
+    // per workgroup there, at G >= 12 it is 3-6 points ahead); otherwise one tile
+    // per workgroup (at 0.3 C: 0.80-0.81 against 0.67-0.77).
     const int64_t wpb = kPhasedBlock / 64;
     const int64_t epu = inf ? 4 : 8;                       // elements per 16-byte unit
+    const int64_t out_esz = outf ? 4 : 2;
     const int64_t n_steps = (count / epu + 63) / 64;
-    int wps = 0;                                           // waves per SIMD; 0 = not phased
-    if (t.reduce_phased == 1) {
-        wps = t.reduce_phase_waves ? static_cast<int>(t.reduce_phase_waves) : (G % kPhasedGroup == 0 ? 1 : 2);
-    } else if (t.reduce_phased == 2) {
-        if (G % kPhasedGroup == 0) wps = (G == 8 && !inf && !outf) ? 2 : 1;
-        else if (G >= 12 || (G >= 3 && inf == outf) || (G >= 5 && inf && !outf)) wps = 2;
-        if (wps && t.reduce_phase_waves) wps = static_cast<int>(t.reduce_phase_waves);
-    }
-    if (wps == 1 && G % kPhasedGroup != 0) wps = 2;        // the one-wave shape is built for full groups only
-    g_last_reduce_shape.store(0, std::memory_order_relaxed);
-    const int64_t W = static_cast<int64_t>(device_cu_count()) * 4 * (wps ? wps : 1);
-    if (wps && aligned && (reinterpret_cast<uintptr_t>(out) & 15u) == 0 &&
-        n_steps >= W * kPhasedMinStepsPerWave) {
-        const int64_t steps_cap = (wps == 1 ? kPhaseSteps1 : kPhaseSteps2) * 4 / epu; // steps a wave holds per phase
-        const int64_t phases = (n_steps + W * steps_cap - 1) / (W * steps_cap);
-        if (phases > 0x7fffffff) return hipErrorInvalidValue;
-        args.phases = static_cast<int32_t>(phases);
-        args.spp = static_cast<int32_t>((n_steps + W * phases - 1) / (W * phases)); // <= steps_cap
+    const int64_t W1 = static_cast<int64_t>(device_cu_count()) * 4; // waves at one per SIMD
+    static_assert(kPhaseSteps1 == 2 * kPhaseSteps2, "both shapes hold the same number of steps per launch");
+    const int64_t cap1 = kPhaseSteps1 * 4 / epu;           // steps a wave holds at one per SIMD
+    const int64_t C = W1 * cap1;                           // steps per launch, either shape
+    const bool can_phase = aligned && (reinterpret_cast<uintptr_t>(out) & 15u) == 0;
+    // waves per SIMD for a launch of `steps` steps; 0 = one tile per workgroup
+    auto shape_for = [&](int64_t steps) {
+        int wps = 0;
+        if (!can_phase) return 0;
+        if (t.reduce_phased == 1) {
+            wps = t.reduce_phase_waves ? static_cast<int>(t.reduce_phase_waves) : (G % kPhasedGroup == 0 ? 1 : 2);
+            if (wps == 1 && G % kPhasedGroup != 0) wps = 2; // the one-wave shape is built for full groups only
+            if (steps < W1 * wps * kPhasedMinStepsPerWave) wps = 0;
+        } else if (t.reduce_phased == 2) {
+            if (G % kPhasedGroup == 0) wps = (G == 8 && !inf && !outf) ? 2 : 1;
+            else if (G >= 12 || (G >= 3 && inf == outf) || (G >= 5 && inf && !outf)) wps = 2;
+            if (wps && t.reduce_phase_waves) wps = static_cast<int>(t.reduce_phase_waves);
+            if (wps == 1 && G % kPhasedGroup != 0) wps = 2;
+            if (wps == 1 && steps * 10 < C * 7) wps = G >= 12 ? 2 : 0;
+            if (wps == 2 && steps * 100 < C * 46) wps = 0;
+        }
+        return wps;
+    };
+    g_last_reduce_shape.store(shape_for(std::min(n_steps, C)), std::memory_order_relaxed);
+    int64_t s_begin = 0;                                   // steps already launched
+    while (s_begin < n_steps) {
+        const int64_t steps = std::min(n_steps - s_begin, C);
+        const int wps = shape_for(steps);
+        if (wps == 0) break;                               // the rest goes to one tile per workgroup
+        const int64_t W = W1 * wps;
         const dim3 g(static_cast<unsigned>(W / wpb)), b(kPhasedBlock);
-        g_last_reduce_shape.store(wps, std::memory_order_relaxed);
-        if (inf && outf) return launch_phased_t<true, true>(args, wps, g, b, st, ev);
-        if (inf && !outf) return launch_phased_t<true, false>(args, wps, g, b, st, ev);
-        if (!inf && outf) return launch_phased_t<false, true>(args, wps, g, b, st, ev);
-        return launch_phased_t<false, false>(args, wps, g, b, st, ev);
+        const int64_t e_begin = s_begin * 64 * epu;        // a multiple of 1 KiB of input: alignment is kept
+        const bool last = s_begin + steps == n_steps;
+        ReduceArgs ra = args;
+        for (int32_t r = 0; r < G; ++r) ra.p[r] = args.p[r] + e_begin * in_esz;
+        ra.out = args.out + e_begin * out_esz;
+        ra.count = last ? count - e_begin : steps * 64 * epu;
+        const int64_t spp = (steps + W - 1) / W;           // <= the steps a wave of this shape holds
+        ra.spp = static_cast<int32_t>(spp);
+        // Runs of 43 or 86 KiB (3 x 43 KiB = 128 KiB + 1 KiB) measured 4-14 % slower than
+        // their neighbours at every G and size tried when all waves start their run
+        // at its first step; started at step w mod spp they run like the neighbours.
+        ra.rotate = t.reduce_phase_rotate == 2 ? 1 : (t.reduce_phase_rotate == 1 ? (spp % 43 == 0) : 0);
+        // with timing on, the call's interval runs from its first dispatch to its last
+        LaunchEvents le;
+        le.start = s_begin == 0 ? ev.start : nullptr;
+        le.stop = last ? ev.stop : nullptr;
+        hipError_t e;
+        if (inf && outf) e = launch_phased_t<true, true>(ra, wps, g, b, st, le);
+        else if (inf && !outf) e = launch_phased_t<true, false>(ra, wps, g, b, st, le);
+        else if (!inf && outf) e = launch_phased_t<false, true>(ra, wps, g, b, st, le);
+        else e = launch_phased_t<false, false>(ra, wps, g, b, st, le);
+        if (e != hipSuccess) return e;
+        s_begin += steps;
     }
-    args.phases = args.spp = 0;
+    if (s_begin >= n_steps && s_begin > 0) return hipSuccess;
+    // one tile per workgroup, for everything or for what the phased launches left
+    const int64_t e_begin = s_begin * 64 * epu;
+    for (int32_t r = 0; r < G; ++r) args.p[r] += e_begin * in_esz;
+    args.out += e_begin * out_esz;
+    args.count = count - e_begin;
+    args.spp = args.rotate = 0;
+    LaunchEvents le;
+    le.start = s_begin == 0 ? ev.start : nullptr;
+    le.stop = ev.stop;
+    const int64_t nvec = args.count >> 2;
     const int64_t block = t.reduce_block;
     int64_t grid = (nvec + block * kReduceUnroll - 1) / (block * kReduceUnroll);
     grid = std::max<int64_t>(1, std::min<int64_t>(grid, 0x7fffffff));
     const dim3 g(static_cast<unsigned>(grid)), b(static_cast<unsigned>(block));
     if (inf && outf)
-        return aligned ? launch_reduce_t<true, true, true>(args, g, b, st, ev)
-                       : launch_reduce_t<true, true, false>(args, g, b, st, ev);
+        return aligned ? launch_reduce_t<true, true, true>(args, g, b, st, le)
+                       : launch_reduce_t<true, true, false>(args, g, b, st, le);
     if (inf && !outf)
-        return aligned ? launch_reduce_t<true, false, true>(args, g, b, st, ev)
-                       : launch_reduce_t<true, false, false>(args, g, b, st, ev);
+        return aligned ? launch_reduce_t<true, false, true>(args, g, b, st, le)
+                       : launch_reduce_t<true, false, false>(args, g, b, st, le);
     if (!inf && outf)
-        return aligned ? launch_reduce_t<false, true, true>(args, g, b, st, ev)
-                       : launch_reduce_t<false, true, false>(args, g, b, st, ev);
-    return aligned ? launch_reduce_t<false, false, true>(args, g, b, st, ev)
-                   : launch_reduce_t<false, false, false>(args, g, b, st, ev);
+        return aligned ? launch_reduce_t<false, true, true>(args, g, b, st, le)
+                       : launch_reduce_t<false, true, false>(args, g, b, st, le);
+    return aligned ? launch_reduce_t<false, false, true>(args, g, b, st, le)
+                   : launch_reduce_t<false, false, false>(args, g, b, st, le);
 }
 
 } // namespace fcdp

@@ -209,13 +209,16 @@ def main():
                     (8, 30007, 0), (9, 1234, 1), (15, 5000, 2), (16, 6553, 0),
                     (17, 4000, 7), (33, 2049, 0), (64, 3001, 11), (5, 3, 0),
                     (5, 0, 0),
-                    # the phased reduce (aligned slices of at least 8 steps per wave; the
-                    # stand-in device has 4 compute units = 16 waves x 104 steps x 256
-                    # elements per phase): one phase, two phases, and the unaligned fallback
-                    (9, 270001, 0), (3, 600007, 0), (3, 600007, 1), (2, 66000, 4),
-                    # full load groups: the one-wave-per-SIMD shape (104 steps held), one
-                    # phase and two (16 waves x 104 steps x 256 elements = 425 984 per phase)
-                    (8, 66003, 0), (16, 140001, 8), (8, 500009, 0)]
+                    # long enough for the rule to pick the phased reduce (the stand-in device
+                    # has 4 compute units: a launch holds 16 waves x 104 steps x 256 elements
+                    # = 425 984): two waves per SIMD, two launches, the unaligned fallback,
+                    # one wave per SIMD
+                    (9, 270001, 0), (3, 600007, 0), (3, 600007, 1), (8, 330003, 0), (16, 700001, 8)]
+    # the phased reduce forced from 8 steps per wave on: both shapes, short runs, a run of
+    # 43 steps per wave (started at step w mod 43), and every run rotated
+    forced_cases = [(2, 66000, 4, 0, 1), (8, 66003, 0, 0, 1), (16, 140001, 8, 0, 1), (8, 500009, 0, 0, 1),
+                    (8, 43 * 16 * 256 - 100, 0, 1, 1), (8, 43 * 16 * 256 - 100, 0, 2, 1),
+                    (24, 300003, 0, 0, 2), (11, 250001, 4, 0, 2), (8, 300003, 0, 0, 2)]
     for G, count, e0 in reduce_cases:
         for in_dt, out_dt in ((oracle.F32, oracle.F32), (oracle.F32, oracle.BF16),
                               (oracle.BF16, oracle.BF16), (oracle.BF16, oracle.F32)):
@@ -223,6 +226,20 @@ def main():
             check_reduce(G, count, e0, in_dt, out_dt, 0)
             check_reduce(G, count, e0, in_dt, out_dt, 0, float(np.float32(1.0 / G)))
             n += 2
+    for G, count, e0, waves, rotate in forced_cases:
+        fcdp.fcdp_tuning_set("reduce_phased", 1)
+        fcdp.fcdp_tuning_set("reduce_phase_waves", waves)
+        fcdp.fcdp_tuning_set("reduce_phase_rotate", rotate)
+        for in_dt, out_dt in ((oracle.F32, oracle.F32), (oracle.F32, oracle.BF16),
+                              (oracle.BF16, oracle.BF16), (oracle.BF16, oracle.F32)):
+            print("reduce, phased forced", G, count, e0, waves, rotate, in_dt, out_dt, flush=True)
+            check_reduce(G, count, e0, in_dt, out_dt, 0)
+            if in_dt == oracle.F32:                 # bf16 steps are twice as long: some cases are too short
+                assert fcdp.fcdp_tuning_get("last_reduce_shape") != 0
+            n += 1
+        fcdp.fcdp_tuning_set("reduce_phased", 2)
+        fcdp.fcdp_tuning_set("reduce_phase_waves", 0)
+        fcdp.fcdp_tuning_set("reduce_phase_rotate", 1)
     for G, tiles in ((1, 2), (5, 7), (8, 3), (19, 2), (64, 1)):
         print("calibration stream", G, tiles, flush=True)
         src = synth.rng(0, G, synth.KIND_GRAD, 3).standard_normal((tiles, G, 1024), dtype=np.float32)

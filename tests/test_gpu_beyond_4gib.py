@@ -126,11 +126,11 @@ def test_layer_with_tensors_and_shards_beyond_4gib():
     H.free()
 
 
-@pytest.mark.parametrize("e0", [5, 8], ids=["one_tile_per_workgroup", "phased_40_phases"])
+@pytest.mark.parametrize("e0", [5, 8], ids=["one_tile_per_workgroup", "phased_40_launches"])
 def test_gradient_slices_beyond_4gib(e0):
     """e0 = 5 leaves the slices unaligned (the one-tile-per-workgroup kernel);
-    e0 = 8 keeps them 16-byte aligned, so the phased kernel runs, 40 phases
-    long at this size."""
+    e0 = 8 keeps them 16-byte aligned, so the phased kernel runs, as 40
+    launches at this size."""
     dev = torch.device("cuda:0")
     G, count = 3, 2 ** 30 + 4099                   # 4 GiB + 16 KiB of fp32 per rank
     parts = [torch.empty(e0 + count + 3, dtype=torch.float32, device=dev) for _ in range(G)]

@@ -282,29 +282,36 @@ def test_reduce_in_place_and_all_ranks():
 # steps per wave (2.1 M fp32 / 4.2 M bf16 elements on 256 compute units), so
 # the small cases above never reach it.  Counts here sit just above that
 # threshold, with ragged tails (count % 4, a partial last step), every
-# remainder of G modulo the load group, and, for G = 2, more than one phase
-# (beyond 27.3 M elements).
+# remainder of G modulo the load group, and, for G = 2, more than one launch
+# (beyond 27.3 M elements).  Knob 1 forces the phased kernel from 8 steps per
+# wave on; knob 2 (the default) leaves the choice to the rule, which wants
+# long launches.
 PHASED_CASES = [
     # G, count, elem_offset, in, out, knob
     (1, 2097152, 0, oracle.F32, oracle.F32, 1),          # exactly 8 steps per wave
     (1, 2097152 - 256, 0, oracle.F32, oracle.F32, 1),    # one step short: the other kernel
     (6, 4194304, 0, oracle.F32, oracle.F32, 1),
     (2, 4194304 + 255, 0, oracle.F32, oracle.BF16, 1),   # partial last step, count % 4 = 3
-    (3, 4300001, 4, oracle.F32, oracle.F32, 2),          # auto rule takes it (fp32 in and out, G >= 3)
-    (5, 4200002, 8, oracle.F32, oracle.F32, 2),
-    (8, 4194304 + 64 * 4 * 7 + 2, 0, oracle.F32, oracle.F32, 2),
+    (3, 4300001, 4, oracle.F32, oracle.F32, 1),
+    (3, 13000001, 4, oracle.F32, oracle.F32, 2),         # the rule takes it (fp32 in and out, G >= 3, 0.48 of a full launch)
+    (5, 4200002, 8, oracle.F32, oracle.F32, 1),
+    (8, 4194304 + 64 * 4 * 7 + 2, 0, oracle.F32, oracle.F32, 1),
+    (8, 20000003, 0, oracle.F32, oracle.BF16, 2),        # the rule: one wave per SIMD
+    (16, 14000005, 8, oracle.BF16, oracle.BF16, 2),      # the rule: half a launch, so two waves per SIMD
     (9, 4250000, 12, oracle.F32, oracle.BF16, 1),
-    (12, 4200003, 0, oracle.F32, oracle.BF16, 2),        # auto rule takes every type pair from G = 12
-    (15, 4194304 + 1, 0, oracle.F32, oracle.F32, 2),
+    (12, 4200003, 0, oracle.F32, oracle.BF16, 1),
+    (15, 4194304 + 1, 0, oracle.F32, oracle.F32, 1),
     (23, 4210000, 16, oracle.BF16, oracle.F32, 1),       # bf16 in, just above its 4.2 M threshold
     (4, 4100000, 8, oracle.BF16, oracle.BF16, 1),        # bf16 in, below it: the other kernel
-    (16, 8388608 + 517, 8, oracle.BF16, oracle.BF16, 2), # bf16 in, 8 elements per lane and step
-    (13, 8400007, 0, oracle.BF16, oracle.F32, 2),
+    (16, 8388608 + 517, 8, oracle.BF16, oracle.BF16, 1), # bf16 in, 8 elements per lane and step
+    (13, 8400007, 0, oracle.BF16, oracle.F32, 1),
     (7, 8388608 + 9, 16, oracle.BF16, oracle.BF16, 1),
-    (32, 4300000, 0, oracle.F32, oracle.BF16, 2),
-    (64, 4194304 + 260, 0, oracle.F32, oracle.F32, 2),
-    (2, 27262976 + 300001, 0, oracle.F32, oracle.F32, 1),   # two phases
-    (2, 3 * 27262976 + 77, 0, oracle.BF16, oracle.BF16, 1), # bf16 in, four phases
+    (32, 4300000, 0, oracle.F32, oracle.BF16, 1),
+    (64, 4194304 + 260, 0, oracle.F32, oracle.F32, 1),
+    (2, 27262976 + 300001, 0, oracle.F32, oracle.F32, 1),   # two launches
+    (2, 3 * 27262976 + 77, 0, oracle.BF16, oracle.BF16, 1), # bf16 in, four launches
+    (8, 22544384 - 1001, 0, oracle.F32, oracle.F32, 2),     # 86 steps per wave: the rotated start
+    (8, 27262976 + 1500001, 0, oracle.F32, oracle.BF16, 2), # a full launch, the rest by one tile per workgroup
     (4, 4300000, 3, oracle.F32, oracle.F32, 1),          # slices not 16-byte aligned: the other kernel
 ]
 
@@ -382,33 +389,41 @@ def test_reduce_phased_both_wave_shapes(G, in_dt, out_dt):
             break                            # the long case once is enough
 
 
-RULE_CASES = [  # G, in, out -> waves per SIMD of the phased kernel, 0 = one tile per workgroup
-    (1, oracle.F32, oracle.F32, 0), (2, oracle.BF16, oracle.BF16, 0),
-    (3, oracle.F32, oracle.F32, 2), (3, oracle.BF16, oracle.BF16, 2), (3, oracle.F32, oracle.BF16, 0),
-    (4, oracle.BF16, oracle.F32, 0), (5, oracle.F32, oracle.BF16, 2), (6, oracle.BF16, oracle.F32, 0),
-    (8, oracle.F32, oracle.F32, 1), (8, oracle.F32, oracle.BF16, 1), (8, oracle.BF16, oracle.F32, 1),
-    (8, oracle.BF16, oracle.BF16, 2), (12, oracle.BF16, oracle.F32, 2),
-    (16, oracle.BF16, oracle.BF16, 1), (16, oracle.F32, oracle.BF16, 1),
+FULL_LAUNCH = 1024 * 104 * 256   # elements one phased launch holds on a 256-CU part
+RULE_CASES = [  # G, in, out, count -> waves per SIMD of the (first) phased launch, 0 = one tile per workgroup
+    (1, oracle.F32, oracle.F32, 20000000, 0), (2, oracle.BF16, oracle.BF16, 20000000, 0),
+    (3, oracle.F32, oracle.F32, 20000000, 2), (3, oracle.BF16, oracle.BF16, 20000000, 2),
+    (3, oracle.F32, oracle.BF16, 20000000, 0), (4, oracle.BF16, oracle.F32, 20000000, 0),
+    (5, oracle.F32, oracle.BF16, 20000000, 2), (6, oracle.BF16, oracle.F32, 20000000, 0),
+    (8, oracle.F32, oracle.F32, 20000000, 1), (8, oracle.F32, oracle.BF16, 20000000, 1),
+    (8, oracle.BF16, oracle.F32, 20000000, 1), (8, oracle.BF16, oracle.BF16, 20000000, 2),
+    (12, oracle.BF16, oracle.F32, 20000000, 2),
+    (16, oracle.BF16, oracle.BF16, 20000000, 1), (16, oracle.F32, oracle.BF16, 20000000, 1),
+    # by length: the one-wave shape from 0.7 of a full launch on; below that two waves per SIMD
+    # for G >= 12 and one tile per workgroup for G = 8; below 0.46 one tile per workgroup
+    (8, oracle.F32, oracle.F32, int(0.55 * FULL_LAUNCH), 0), (16, oracle.BF16, oracle.BF16, int(0.55 * FULL_LAUNCH), 2),
+    (32, oracle.F32, oracle.BF16, int(0.50 * FULL_LAUNCH), 2), (12, oracle.F32, oracle.F32, int(0.50 * FULL_LAUNCH), 2),
+    (16, oracle.F32, oracle.F32, int(0.40 * FULL_LAUNCH), 0), (12, oracle.F32, oracle.F32, int(0.40 * FULL_LAUNCH), 0),
+    # beyond one launch: full launches, then the rest judged by its own length
+    (8, oracle.F32, oracle.F32, int(1.05 * FULL_LAUNCH), 1), (8, oracle.F32, oracle.F32, int(1.80 * FULL_LAUNCH), 1),
 ]
 
 
-@pytest.mark.parametrize("G,in_dt,out_dt,shape", RULE_CASES)
-def test_reduce_rule_picks_the_documented_shape(G, in_dt, out_dt, shape):
+@pytest.mark.parametrize("G,in_dt,out_dt,count,shape", RULE_CASES)
+def test_reduce_rule_picks_the_documented_shape(G, in_dt, out_dt, count, shape):
     """Left to its rule (the default), the reduce launches the kernel shape the
-    header documents for this rank count and type pair; an input too short
-    for the persistent grid takes one tile per workgroup whatever the rule."""
+    header documents for this rank count, type pair and length."""
+    if torch.cuda.get_device_properties(0).multi_processor_count != 256:
+        pytest.skip("the lengths here are fractions of a launch on a 256-CU part")
     assert fcdp.fcdp_tuning_get("reduce_phased") == 2 and fcdp.fcdp_tuning_get("reduce_phase_waves") == 0
     ies = 4 if in_dt == oracle.F32 else 2
-    count = 4300000 * (4 // ies)
     buf = torch.zeros(count * ies, dtype=torch.uint8, device="cuda")   # every rank reads the same zeros
     out = torch.empty(count * 4, dtype=torch.uint8, device="cuda")
     ptrs = [buf.data_ptr()] * G
     fcdp.fcdp_reduce_grad_shard(ptrs, G, 0, count, in_dt, out_dt, out.data_ptr(), None)
     torch.cuda.synchronize()
     assert fcdp.fcdp_tuning_get("last_reduce_shape") == shape
-    fcdp.fcdp_reduce_grad_shard(ptrs, G, 0, 100000, in_dt, out_dt, out.data_ptr(), None)
-    torch.cuda.synchronize()
-    assert fcdp.fcdp_tuning_get("last_reduce_shape") == 0
+    assert not bool(out[:count * (4 if out_dt == oracle.F32 else 2)].view(torch.int16).bitwise_and(0x7fff).any())  # sums of zeros
 
 
 def test_reduce_phased_specials_in_place_and_both_kernels_agree():
