@@ -375,7 +375,7 @@ def reduce_sweep(fcdp, torch, S=25297920):
     dev = torch.device("cuda:0")
     st = torch.cuda.Stream()
     before = (fcdp.fcdp_tuning_get("reduce_phased"), fcdp.fcdp_tuning_get("reduce_phase_waves"))
-    rows = []
+    rows, by_length = [], []
     try:
         for G in (1, 2, 3, 4, 6, 8, 9, 10, 12, 14, 16, 20, 24, 32, 40, 64):
             NB = 3
@@ -406,11 +406,41 @@ def reduce_sweep(fcdp, torch, S=25297920):
                     rows.append(row)
                     log("G=%d %s -> %s: %s" % (G, iname, oname, {k: v for k, v in row.items() if k not in ("G", "in", "out")}))
             del ps, outs
+        # by length: one tile per workgroup against the rule's pick, fp32 partials
+        for G in (8, 12, 16, 32):
+            for S2 in (8000000, 13000000, 15000000, 17000000, 20000000, 22544384, 25297920, 27264000,
+                       30000000, 40000000, 47000000, 60000000, 100000000):
+                if G * S2 * 4 * 2 > 30e9:
+                    continue
+                NB = 2
+                ps = [torch.empty(G, S2, dtype=torch.float32, device=dev).normal_(0, 1e-3) for _ in range(NB)]
+                ptrs = [fcdp.pointer_array([p.data_ptr() + r * S2 * 4 for r in range(G)]) for p in ps]
+                outs = [torch.empty(S2, dtype=torch.float32, device=dev) for _ in range(NB)]
+                for odt, oname, osz in ((fcdp.F32, "fp32", 4), (fcdp.BF16, "bf16", 2)):
+                    row = {"G": G, "S": S2, "out": oname}
+                    for name, phased in (("tiles", 0), ("rule", 2)):
+                        fcdp.fcdp_tuning_set("reduce_phased", phased)
+                        fcdp.fcdp_tuning_set("reduce_phase_waves", 0)
+                        reps = 12
+                        for i in range(2):
+                            fcdp.fcdp_reduce_grad_shard(ptrs[i % NB], G, 0, S2, fcdp.F32, odt, outs[i % NB], st)
+                        torch.cuda.synchronize()
+                        fcdp.fcdp_timing_enable(reps + 4)
+                        for i in range(reps):
+                            fcdp.fcdp_reduce_grad_shard(ptrs[i % NB], G, 0, S2, fcdp.F32, odt, outs[i % NB], st)
+                        torch.cuda.synchronize()
+                        n, ms = fcdp.fcdp_timing_collect(fcdp.KERNEL_REDUCE)   # one interval per call
+                        fcdp.fcdp_timing_enable(0)
+                        row[name] = round((G * S2 * 4 + S2 * osz) / (ms / n * 1e-3) / 1e9 / HBM_PEAK_GBPS, 3)
+                    row["rule_shape"] = fcdp.fcdp_tuning_get("last_reduce_shape")
+                    by_length.append(row)
+                    log("G=%d S=%d -> %s: %s" % (G, S2, oname, {k: v for k, v in row.items() if k not in ("G", "S", "out")}))
+                del ps, outs
     finally:
         fcdp.fcdp_tuning_set("reduce_phased", before[0])
         fcdp.fcdp_tuning_set("reduce_phase_waves", before[1])
-    print(json.dumps({"study": "reduce kernels over G and type pairs, fractions of the HBM peak", "S": S,
-                      "peak_gbps": HBM_PEAK_GBPS, "rows": rows}), flush=True)
+    print(json.dumps({"study": "reduce kernels over G and type pairs, and over lengths; fractions of the HBM peak",
+                      "S": S, "peak_gbps": HBM_PEAK_GBPS, "rows": rows, "by_length": by_length}), flush=True)
 
 
 def main():
