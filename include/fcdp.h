@@ -480,16 +480,20 @@ const char *fcdp_last_error(void);
  *                         boundary, so normal operation cannot check them).
  * Read only (fcdp_tuning_set answers FCDP_EINVAL, as for an unknown name):
  *   last_reduce_shape     what the last fcdp_reduce_grad_shard[_scaled] of the
- *                         process launched: 0 one tile per workgroup, 1 or 2
- *                         the phased kernel with that many waves per SIMD */
+ *                         process launched (first, if it took several
+ *                         launches): 0 one tile per workgroup, 1 or 2 the
+ *                         phased kernel with that many waves per SIMD */
 fcdp_status fcdp_tuning_set(const char *name, int64_t value);
 int64_t fcdp_tuning_get(const char *name); /* -1 if unknown */
 
 /* Kernel timing for measurement.  While enabled, every kernel dispatch the
  * library makes on the current device carries a start and a stop event that
  * take the dispatch's own begin and end timestamps on its stream (at most
- * `capacity` dispatches are kept; later ones are not timed).  fcdp_timing_collect waits for the recorded launches of
- * one kind, returns how many there were and the sum of their durations in
+ * `capacity` dispatches are kept; later ones are not timed).  A reduce that
+ * takes several dispatches (an input longer than one launch of the phased
+ * kernel holds) counts as one: its start is taken on the first dispatch and
+ * its stop on the last.  fcdp_timing_collect waits for the recorded launches
+ * of one kind, returns how many there were and the sum of their durations in
  * milliseconds, and forgets them.  fcdp_timing_enable(0) disables timing and
  * frees the events.  Not thread-safe against concurrent data calls. */
 typedef enum {

@@ -34,6 +34,9 @@ class Arena:
         self.buf = torch.full((self.total,), SENTINEL, dtype=torch.uint8, device="cuda")
         self.base = self.buf.data_ptr()
         assert self.base % 16 == 0
+        # the fill ran on torch's stream; the library's calls run on streams of the
+        # caller's choice, which do not wait for it
+        torch.cuda.synchronize()
 
     def ptr(self, i):
         return self.base + self.ranges[i][0]
@@ -47,6 +50,7 @@ class Arena:
         assert b.size == nb
         if nb:
             self.buf[o:o + nb] = torch.from_numpy(b.copy()).cuda()
+            torch.cuda.synchronize()
 
     def get(self, i, dtype) -> np.ndarray:
         o, nb = self.ranges[i]

@@ -72,6 +72,7 @@ def test_full_layer_materialize_and_reduce(name, layer):
         # PEFT shape: pack, then unpack updated values; frozen bytes untouched
         d_flat = torch.from_numpy(flat.view(np.int16).copy()).to(dev)
         packed = torch.zeros(L.packed_numel, dtype=torch.int16, device=dev)
+        torch.cuda.synchronize()                  # the fill runs on torch's stream, the library on `compute`
         fcdp.fcdp_pack_trainable(L, d_flat, packed, compute)
         torch.cuda.synchronize()
         assert np.array_equal(packed.cpu().numpy().view(np.uint16),
