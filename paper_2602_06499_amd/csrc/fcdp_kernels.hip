@@ -489,10 +489,7 @@ __global__ void __launch_bounds__(64) reduce_stream_calibration(const StreamArgs
 constexpr int kPhasedBlock = 256;                          // four waves
 constexpr int kPhaseSteps1 = 104, kPhaseSteps2 = 52;       // steps of 4 elements per lane held per phase
 constexpr int kPhasedMinStepsPerWave = 8; // below this the one-tile-per-workgroup kernel is used
-#ifndef FCDP_PHASE_GROUP
-#define FCDP_PHASE_GROUP 8
-#endif
-constexpr int kPhasedGroup = FCDP_PHASE_GROUP; // partials loaded back to back before their adds
+constexpr int kPhasedGroup = 8; // partials loaded back to back before their adds (4 or 6 measured 1-3 % slower)
 
 // One lane's share of a step: 16 bytes of one partial = E elements (4 fp32
 // or 8 bf16), widened to fp32 only when they are added, so that the loads of
