@@ -86,8 +86,9 @@ def test_poison_is_written_first(poison):
             if np.all(got == 0x7FC1):
                 states.append("poison")
             else:
-                # a snapshot that ran late sees the finished layer, never stale bytes
-                assert np.array_equal(got, want), "tensor holds neither the pattern nor the layer"
+                # a snapshot that ran late sees the layer, or, if it ran beside the scatter,
+                # the layer where the scatter has been and the pattern elsewhere; never stale bytes
+                assert np.all((got == want) | (got == 0x7FC1)), "tensor holds neither the pattern nor the layer"
                 states.append("layer")
         poisoned += all(st == "poison" for st in states)
     assert poisoned >= 1, "no snapshot saw the tensors poisoned ahead of the fetch"
