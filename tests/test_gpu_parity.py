@@ -312,6 +312,7 @@ PHASED_CASES = [
     (2, 3 * 27262976 + 77, 0, oracle.BF16, oracle.BF16, 1), # bf16 in, four launches
     (8, 22544384 - 1001, 0, oracle.F32, oracle.F32, 2),     # 86 steps per wave: the rotated start
     (8, 27262976 + 1500001, 0, oracle.F32, oracle.BF16, 2), # a full launch, the rest by one tile per workgroup
+    (8, 2 * 27262976 + 21000003, 4, oracle.F32, oracle.F32, 2), # two full launches and a third of 0.77 of one
     (4, 4300000, 3, oracle.F32, oracle.F32, 1),          # slices not 16-byte aligned: the other kernel
 ]
 
