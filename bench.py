@@ -143,7 +143,7 @@ class Stack:
     """Device and host buffers of one stack, and its step."""
 
     def __init__(self, fcdp, synth, torch, cfg_name, layers, cache, arena_bytes, cache_slots, grad_slots,
-                 fetch, store, out_f32, tau=0.0):
+                 fetch, store, out_f32, tau=0.0, node_g=1):
         self.fcdp, self.torch = fcdp, torch
         dev = torch.device("cuda:0")
         cfg = synth.CONFIGS[cfg_name]
@@ -154,14 +154,20 @@ class Stack:
         self.N, self.Np, self.S = self.lay.numel, self.lay.padded_numel, self.lay.shard_numel
         N, Np, S = self.N, self.Np, self.S
         self.layer_bytes = Np * 2
-        fit = max(1, int(arena_bytes // self.layer_bytes))
+        # node_g > 1: this GPU is one of node_g in its node and caches shards [0, G / node_g)
+        # of every layer (Sec. 4.3); the other shards are on the device already, as the
+        # exchange inside the node would leave them
+        assert G % node_g == 0 and (node_g == 1 or (tau == 0 and fetch == "dma" and store == "dma"))
+        self.node_g, self.n_own = node_g, G // node_g
+        self.slot_bytes = self.n_own * S * 2
+        fit = max(1, int(arena_bytes // self.slot_bytes))
         self.K = min(L, cache_slots or fit, fit)
         self.Kg = min(L, max(1, grad_slots))
         self.fetch, self.store, self.out_f32, self.tau = fetch, store, out_f32, tau
         self.cache = cache
         log("%s: %d layers, N=%d, G=%d, S=%d, %.1f MB/layer; host cache ring of %d slots (%.2f GB), "
             "%d layers of gradient partials on the device"
-            % (cfg.name, L, N, G, S, self.layer_bytes / 1e6, self.K, self.K * self.layer_bytes / 1e9, self.Kg))
+            % (cfg.name, L, N, G, S, self.layer_bytes / 1e6, self.K, self.K * self.slot_bytes / 1e9, self.Kg))
         # ---- inputs, resident before timing ----
         self.gathered = []       # slot k: the G shards of layers l = k (mod K) as one gather buffer
         for k in range(self.K):
@@ -178,7 +184,7 @@ class Stack:
             p.normal_(0.0, 1e-3, generator=g)
             self.partials.append(p)
         self.tensors = [torch.empty(max(k, 1), dtype=torch.bfloat16, device=dev) for k in cfg.numel]
-        self.staging = [torch.empty(Np, dtype=torch.bfloat16, device=dev) for _ in range(2)]
+        self.staging = [torch.empty(self.n_own * S, dtype=torch.bfloat16, device=dev) for _ in range(2)]
         self.grad_shard = torch.empty(S, dtype=torch.float32 if out_f32 else torch.bfloat16, device=dev)
         self.state = fcdp.CacheState(L)
         self.state.set_tau(tau)
@@ -205,7 +211,7 @@ class Stack:
         torch.cuda.synchronize()
 
     def slot(self, l):
-        return self.cache.host + (l % self.K) * self.layer_bytes
+        return self.cache.host + (l % self.K) * self.slot_bytes
 
     def step(self, record):
         """record: None, or a list that collects the sweep events."""
@@ -217,7 +223,13 @@ class Stack:
         for l in range(self.L):
             src, _ = st.forward_source(l, 1, self.host_mode)          # full fine-tuning: always a miss
             tp = self.kept_sets.get(l, self.tensor_ptrs)
-            if self.tau > 0:
+            if self.node_g > 1:
+                fcdp.fcdp_materialize_layer(lay, src, self.shard_ptrs[l % K], None, None, tp,
+                                            fcdp.STORE_NONE, compute, copy)
+                fcdp.fcdp_cache_store_node_slice(lay, 0, self.n_own, self.shard_ptrs[l % K], self.slot(l),
+                                                 compute, copy)
+                st.place(l, self.total_mem, self.total_mem)
+            elif self.tau > 0:
                 fcdp.fcdp_materialize_layer(lay, src, self.shard_ptrs[l % K], None, None, tp,
                                             fcdp.STORE_NONE, compute, copy)
                 # (the layer's forward computation would run here)
@@ -232,8 +244,12 @@ class Stack:
             e1 = ev(enable_timing=True); e1.record(copy if self.tau < 1.0 else compute)
         for l in range(self.L - 1, -1, -1):
             src = st.backward_source(l, 1, self.host_mode)
-            fcdp.fcdp_materialize_layer(lay, src, None, self.slot(l), self.staging[l % 2],
-                                        self.kept_sets.get(l, self.tensor_ptrs), False, compute, copy)
+            if self.node_g > 1:
+                fcdp.fcdp_materialize_layer_node_slice(lay, 0, self.n_own, self.shard_ptrs[l % K], self.slot(l),
+                                                       self.staging[l % 2], self.tensor_ptrs, compute, copy)
+            else:
+                fcdp.fcdp_materialize_layer(lay, src, None, self.slot(l), self.staging[l % 2],
+                                            self.kept_sets.get(l, self.tensor_ptrs), False, compute, copy)
             st.release(l)
             fcdp.fcdp_reduce_grad_shard(self.part_ptrs[l % Kg], G, 0, S, fcdp.F32, self.out_dt,
                                         self.grad_shard, compute)
@@ -303,8 +319,9 @@ class Stack:
         import numpy as np
         k = (self.L - 1) % self.K
         if (self.L - 1) not in self.kept_sets:
-            hc = torch.from_numpy(self.cache.numpy(np.int16, self.Np, k * self.layer_bytes))
-            assert torch.equal(hc, self.gathered[k].cpu().view(torch.int16)), "host cache mismatch"
+            n = self.n_own * self.S
+            hc = torch.from_numpy(self.cache.numpy(np.int16, n, k * self.slot_bytes))
+            assert torch.equal(hc, self.gathered[k][:n].cpu().view(torch.int16)), "host cache mismatch"
 
     def free(self):
         self.gathered = self.partials = self.tensors = self.staging = None
@@ -587,6 +604,38 @@ def main():
             log("%s: %.1f ms/step" % (name, r["ms_per_step"]))
             s2.free()
             del s2
+
+    # ---- one GPU of a node of 8 (Sec. 4.3: it caches and fetches 1/8 of every layer; the other
+    # 7/8 are on the device already, as the exchange inside the node would leave them) ----
+    if not args.no_legs:
+        node_g = 8
+        s3 = Stack(fcdp, synth, torch, "llama70b_g32", 0, cache, arena_bytes, args.cache_slots or 15, args.grad_slots,
+                   "dma", "dma", False, node_g=node_g)
+        r = s3.run(args.leg_steps, args.leg_warmup)
+        if not args.no_check:
+            s3.check()
+        per_layer_ms = r["bwd_ms"] / s3.L
+        fetch_ms = s3.slot_bytes / (link["h2d"] * 1e9) * 1e3
+        kern_ms = r["k1_ms"] + r["k3_ms"]
+        legs["llama70b_g32_node_of_8"] = {
+            "workload": "llama70b_g32: %d layers of %.1f MB, G=%d, this GPU one of %d in its node: it stores and "
+                        "fetches shards 0..%d of every layer (%.1f MB), the other shards are on the device; "
+                        "host cache of %d slots (%.2f GB), bf16 shard out"
+                        % (s3.L, s3.layer_bytes / 1e6, s3.cfg.G, node_g, s3.n_own - 1, s3.slot_bytes / 1e6, s3.K,
+                           s3.K * s3.slot_bytes / 1e9),
+            "steps": args.leg_steps, "ms_per_step": round(r["ms_per_step"], 2),
+            "materialized_gbps": round(r["value"], 2),
+            "link_bytes_per_layer": s3.slot_bytes,
+            "store_d2h_gbps": round(r["d2h_gbps"], 2), "fetch_h2d_gbps": round(r["h2d_gbps"], 2),
+            "backward_ms_per_layer": round(per_layer_ms, 3),
+            "overlap_efficiency": round(max(fetch_ms, kern_ms) / per_layer_ms, 4),
+            "kernels_ms_per_backward_layer": round(kern_ms, 3),
+            "unflatten_us": round(1e3 * r["k1_ms"], 1), "unflatten_frac": round(r["k1_gbps"] / HBM_PEAK_GBPS, 4),
+            "reduce_us": round(1e3 * r["k3_ms"], 1), "reduce_frac": round(r["k3_gbps"] / HBM_PEAK_GBPS, 4),
+        }
+        log("llama70b_g32_node_of_8: %.1f ms/step" % r["ms_per_step"])
+        s3.free()
+        del s3
 
     # ---- PEFT leg: LoRA r16 on q,v of the 7B-shaped stack ----
     peft = cpu_peft = None

@@ -244,6 +244,50 @@ fcdp_status fcdp_cache_store(const fcdp_layout *layout,
                              int store_mode, fcdp_stream compute,
                              fcdp_stream copy);
 
+/* One GPU's share when a node has g GPUs (Sec. 4.3, backward pass: each GPU
+ * loads its 1/g part of the cached layer from host memory over its own link,
+ * then the node's GPUs exchange their parts; Sec. 5.1: the node caches the
+ * layer once, about 2W bytes per node).  This GPU's part is the n_shards
+ * consecutive rank shards [first_shard, first_shard + n_shards), n_shards =
+ * G/g in the paper's setting (any 1..G here).
+ *
+ * fcdp_cache_store_node_slice: host_slice <- shard_first .. shard_{first +
+ * n_shards - 1} by DMA on `copy`, ordered after what is enqueued on `compute`.
+ *   shard_ptrs   host array of G dev ptrs; only the entries of the slice are
+ *                read (the others may be NULL)
+ *   host_slice   pinned host ptr, n_shards*S*elem_size bytes
+ *
+ * fcdp_materialize_layer_node_slice: the layer's tensors from this GPU's
+ * cached part and the parts the peers delivered.  host_slice is copied to
+ * staging_slice on `copy` (with the same staging-buffer bookkeeping as
+ * FCDP_SRC_HOST_DMA, so two staging slices alternate without host waits),
+ * then one scatter on `compute` reads the slice's shards from staging_slice
+ * and every other shard from shard_ptrs.
+ *   shard_ptrs     host array of G dev ptrs; entries outside the slice are
+ *                  the peers' shards, S*elem_size bytes each, valid in
+ *                  compute-stream order (how they got there -- an exchange
+ *                  over the node's links -- is not this library's business);
+ *                  entries inside the slice are ignored
+ *   host_slice     pinned host ptr, n_shards*S*elem_size bytes
+ *   staging_slice  dev ptr, n_shards*S*elem_size bytes
+ * Over the host link go n_shards*S*elem_size bytes per call (fcdp_link_bytes
+ * counts that).  Errors: FCDP_EINVAL (NULL, a slice outside [0, G)),
+ * FCDP_EALIGN, FCDP_ENOTPINNED, FCDP_EHIP. */
+fcdp_status fcdp_cache_store_node_slice(const fcdp_layout *layout,
+                                        int32_t first_shard, int32_t n_shards,
+                                        const void *const *shard_ptrs,
+                                        void *host_slice, fcdp_stream compute,
+                                        fcdp_stream copy);
+fcdp_status fcdp_materialize_layer_node_slice(const fcdp_layout *layout,
+                                              int32_t first_shard,
+                                              int32_t n_shards,
+                                              const void *const *shard_ptrs,
+                                              void *host_slice,
+                                              void *staging_slice,
+                                              void *const *tensor_ptrs,
+                                              fcdp_stream compute,
+                                              fcdp_stream copy);
+
 /* Inverse of the scatter, for initialisation and tests: writes the G shards
  * from the T tensors and zero-fills the tail padding. */
 fcdp_status fcdp_flatten_to_shards(const fcdp_layout *layout,

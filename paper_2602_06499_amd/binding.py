@@ -43,6 +43,7 @@ EXPORTS = [
     "fcdp_layout_prepare",
     "fcdp_materialize_layer", "fcdp_materialize_layer_static",
     "fcdp_cache_store", "fcdp_flatten_to_shards",
+    "fcdp_cache_store_node_slice", "fcdp_materialize_layer_node_slice",
     "fcdp_reduce_grad_shard", "fcdp_reduce_trainable_shard",
     "fcdp_reduce_grad_shard_scaled", "fcdp_reduce_trainable_shard_scaled",
     "fcdp_pack_trainable", "fcdp_unpack_trainable",
@@ -105,6 +106,8 @@ def load_library() -> ctypes.CDLL:
     lib.fcdp_materialize_layer_static.argtypes = [vp, vp, vp, vp, vp]
     lib.fcdp_flatten_to_shards.argtypes = [vp, vp, vp, vp]
     lib.fcdp_cache_store.argtypes = [vp, vp, vp, c.c_int, vp, vp]
+    lib.fcdp_cache_store_node_slice.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+    lib.fcdp_materialize_layer_node_slice.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.fcdp_cache_state_set_tau.argtypes = [vp, c.c_double]
     lib.fcdp_cache_state_place.argtypes = [vp, i32, i64, i64, c.POINTER(i32)]
     lib.fcdp_cache_state_release.argtypes = [vp, i32]
@@ -268,6 +271,21 @@ def fcdp_cache_store(layout: Layout, shard_ptrs, host_cache, store_mode=STORE_DM
     _check(load_library().fcdp_cache_store(
         layout.handle, _ptr_array(shard_ptrs), _ptr(host_cache), int(store_mode),
         _stream(compute), _stream(copy)))
+
+
+def fcdp_cache_store_node_slice(layout: Layout, first_shard: int, n_shards: int, shard_ptrs,
+                                host_slice, compute=None, copy=None) -> None:
+    _check(load_library().fcdp_cache_store_node_slice(
+        layout.handle, first_shard, n_shards, _ptr_array(shard_ptrs), _ptr(host_slice),
+        _stream(compute), _stream(copy)))
+
+
+def fcdp_materialize_layer_node_slice(layout: Layout, first_shard: int, n_shards: int, shard_ptrs,
+                                      host_slice, staging_slice, tensor_ptrs,
+                                      compute=None, copy=None) -> None:
+    _check(load_library().fcdp_materialize_layer_node_slice(
+        layout.handle, first_shard, n_shards, _ptr_array(shard_ptrs), _ptr(host_slice),
+        _ptr(staging_slice), _ptr_array(tensor_ptrs), _stream(compute), _stream(copy)))
 
 
 def fcdp_link_bytes(reset: bool = False):

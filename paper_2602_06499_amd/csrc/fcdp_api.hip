@@ -391,13 +391,15 @@ fcdp_status poison_tensors(const fcdp_layout *L, void *const *tensor_ptrs, hipSt
 
 // H <- concat(shards): after the producers of the shards (everything on
 // `compute` so far), on the `copy` stream.
-fcdp_status enqueue_store(const fcdp_layout *L, DeviceCtx *ctx, const void *const *shard_ptrs,
+// `shard_ptrs` are the n_shards consecutive shards whose image `host_cache`
+// takes (all G of them for a whole layer).
+fcdp_status enqueue_store(const fcdp_layout *L, DeviceCtx *ctx, const void *const *shard_ptrs, int32_t n_shards,
                           void *host_cache, void *store_alias, int store_cache,
                           hipStream_t compute, hipStream_t copy)
 {
     const fcdp::Tuning &tune = fcdp::tuning();
-    const size_t flat_bytes = static_cast<size_t>(L->N_pad) * L->esz;
     const size_t shard_bytes = static_cast<size_t>(L->S) * L->esz;
+    const size_t flat_bytes = shard_bytes * static_cast<size_t>(n_shards);
     fcdp_status st;
     // H <- concat(shards): after the producers of the shards, beside the scatter
     if ((st = order_after(ctx, compute, copy)) != FCDP_OK) return st;
@@ -411,7 +413,7 @@ fcdp_status enqueue_store(const fcdp_layout *L, DeviceCtx *ctx, const void *cons
     }
     // contiguous shards (one gather buffer) go out as a single copy
     bool contiguous = true;
-    for (int32_t r = 1; r < L->G; ++r)
+    for (int32_t r = 1; r < n_shards; ++r)
         if (static_cast<const char *>(shard_ptrs[r]) != static_cast<const char *>(shard_ptrs[0]) + r * shard_bytes)
             contiguous = false;
     if (store_cache == FCDP_STORE_ZEROCOPY) {
@@ -423,7 +425,7 @@ fcdp_status enqueue_store(const fcdp_layout *L, DeviceCtx *ctx, const void *cons
         shape.max_wgs = tune.link_max_wgs;
         shape.nt = 0;
         char *ha = static_cast<char *>(store_alias);
-        const int32_t n_copies = contiguous ? 1 : L->G;
+        const int32_t n_copies = contiguous ? 1 : n_shards;
         const size_t each = contiguous ? flat_bytes : shard_bytes;
         for (int32_t r = 0; r < n_copies; ++r) {
             shape.ev = timing_events(FCDP_KERNEL_STORE_ZEROCOPY);
@@ -435,7 +437,7 @@ fcdp_status enqueue_store(const fcdp_layout *L, DeviceCtx *ctx, const void *cons
         FCDP_HIP(hipMemcpyAsync(h, shard_ptrs[0], flat_bytes, hipMemcpyDeviceToHost, copy), "hipMemcpyAsync(D2H)");
         if ((st = copy_enqueued(ctx, copy)) != FCDP_OK) return st;
     } else {
-        for (int32_t r = 0; r < L->G; ++r) {
+        for (int32_t r = 0; r < n_shards; ++r) {
             if ((st = copy_admit(ctx)) != FCDP_OK) return st;
             FCDP_HIP(hipMemcpyAsync(h + r * shard_bytes, shard_ptrs[r], shard_bytes, hipMemcpyDeviceToHost, copy), "hipMemcpyAsync(D2H)");
             if ((st = copy_enqueued(ctx, copy)) != FCDP_OK) return st;
@@ -595,7 +597,7 @@ try {
     const void *small[FCDP_MAX_G];
     if (src == FCDP_SRC_DEVICE_SHARDS) {
         if (store_cache && flat_bytes) {
-            if ((st = enqueue_store(L, ctx, shard_ptrs, host_cache, store_alias, store_cache, compute, copy)) != FCDP_OK)
+            if ((st = enqueue_store(L, ctx, shard_ptrs, L->G, host_cache, store_alias, store_cache, compute, copy)) != FCDP_OK)
                 return st;
         }
         for (int32_t r = 0; r < L->G; ++r) small[r] = shard_ptrs[r];
@@ -747,10 +749,121 @@ try {
         return st;
     DeviceCtx *ctx = nullptr;
     if ((st = current_ctx(&ctx)) != FCDP_OK) return st;
-    return enqueue_store(L, ctx, shard_ptrs, host_cache, alias, store_mode,
+    return enqueue_store(L, ctx, shard_ptrs, L->G, host_cache, alias, store_mode,
                          static_cast<hipStream_t>(compute_), static_cast<hipStream_t>(copy_));
 } catch (...) {
     return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_cache_store: out of host memory");
+}
+
+// ------------------------------------------------ one GPU's share of a node
+namespace {
+fcdp_status check_node_slice(const fcdp_layout *L, int32_t first_shard, int32_t n_shards, const char *fn)
+{
+    if (first_shard < 0 || n_shards < 1 || first_shard > L->G - n_shards)
+        return fail(FCDP_EINVAL, std::string(fn) + ": shards [first_shard, first_shard + n_shards) must lie in [0, G)");
+    return FCDP_OK;
+}
+} // namespace
+
+fcdp_status fcdp_cache_store_node_slice(const fcdp_layout *L, int32_t first_shard, int32_t n_shards,
+                                        const void *const *shard_ptrs, void *host_slice,
+                                        fcdp_stream compute_, fcdp_stream copy_)
+try {
+    const char *fn = "fcdp_cache_store_node_slice";
+    if (!L) return fail(FCDP_EINVAL, std::string(fn) + ": layout is NULL");
+    fcdp_status st = check_node_slice(L, first_shard, n_shards, fn);
+    if (st != FCDP_OK) return st;
+    if (!shard_ptrs) return fail(FCDP_EINVAL, std::string(fn) + ": shard_ptrs is NULL");
+    for (int32_t r = first_shard; r < first_shard + n_shards; ++r) {
+        if (!shard_ptrs[r]) return fail(FCDP_EINVAL, std::string(fn) + ": a shard pointer of the slice is NULL");
+        if (!aligned16(shard_ptrs[r])) return fail(FCDP_EALIGN, std::string(fn) + ": a shard pointer is not 16-byte aligned");
+    }
+    if (!host_slice) return fail(FCDP_EINVAL, std::string(fn) + ": host_slice is NULL");
+    if (!aligned16(host_slice)) return fail(FCDP_EALIGN, std::string(fn) + ": host_slice is not 16-byte aligned");
+    const size_t slice_bytes = static_cast<size_t>(L->S) * L->esz * static_cast<size_t>(n_shards);
+    if (slice_bytes == 0) return FCDP_OK;
+    if ((st = require_pinned(host_slice, slice_bytes, fn)) != FCDP_OK) return st;
+    DeviceCtx *ctx = nullptr;
+    if ((st = current_ctx(&ctx)) != FCDP_OK) return st;
+    if (fcdp::tuning().debug_poison)
+        for (int32_t r = first_shard; r < first_shard + n_shards; ++r)
+            if ((st = check_extent(shard_ptrs[r], static_cast<size_t>(L->S) * L->esz, fn, "a shard")) != FCDP_OK) return st;
+    return enqueue_store(L, ctx, shard_ptrs + first_shard, n_shards, host_slice, nullptr, FCDP_STORE_DMA,
+                         static_cast<hipStream_t>(compute_), static_cast<hipStream_t>(copy_));
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_cache_store_node_slice: out of host memory");
+}
+
+fcdp_status fcdp_materialize_layer_node_slice(const fcdp_layout *L, int32_t first_shard, int32_t n_shards,
+                                              const void *const *shard_ptrs, void *host_slice,
+                                              void *staging_slice, void *const *tensor_ptrs,
+                                              fcdp_stream compute_, fcdp_stream copy_)
+try {
+    const char *fn = "fcdp_materialize_layer_node_slice";
+    if (!L) return fail(FCDP_EINVAL, std::string(fn) + ": layout is NULL");
+    fcdp_status st = check_node_slice(L, first_shard, n_shards, fn);
+    if (st != FCDP_OK) return st;
+    if ((st = check_tensor_ptrs(L, reinterpret_cast<const void *const *>(tensor_ptrs), fn)) != FCDP_OK) return st;
+    if (!shard_ptrs && n_shards < L->G) return fail(FCDP_EINVAL, std::string(fn) + ": shard_ptrs is NULL");
+    for (int32_t r = 0; r < L->G; ++r) {
+        if (r >= first_shard && r < first_shard + n_shards) continue; // the slice comes from the host
+        if (!shard_ptrs[r]) return fail(FCDP_EINVAL, std::string(fn) + ": a shard pointer outside the slice is NULL");
+        if (!aligned16(shard_ptrs[r])) return fail(FCDP_EALIGN, std::string(fn) + ": a shard pointer is not 16-byte aligned");
+    }
+    if (!host_slice) return fail(FCDP_EINVAL, std::string(fn) + ": host_slice is NULL");
+    if (!aligned16(host_slice)) return fail(FCDP_EALIGN, std::string(fn) + ": host_slice is not 16-byte aligned");
+    if (!staging_slice) return fail(FCDP_EINVAL, std::string(fn) + ": staging_slice is NULL");
+    if (!aligned16(staging_slice)) return fail(FCDP_EALIGN, std::string(fn) + ": staging_slice is not 16-byte aligned");
+    const size_t shard_bytes = static_cast<size_t>(L->S) * L->esz;
+    const size_t slice_bytes = shard_bytes * static_cast<size_t>(n_shards);
+    if (L->N == 0) return FCDP_OK;
+    if ((st = require_pinned(host_slice, slice_bytes, fn)) != FCDP_OK) return st;
+    hipStream_t compute = static_cast<hipStream_t>(compute_);
+    hipStream_t copy = static_cast<hipStream_t>(copy_);
+    DeviceCtx *ctx = nullptr;
+    if ((st = current_ctx(&ctx)) != FCDP_OK) return st;
+    const fcdp::DeviceTables *tabs = nullptr;
+    if ((st = tables_for_current_device(L, &tabs)) != FCDP_OK) return st;
+    const fcdp::Tuning &tune = fcdp::tuning();
+    if (tune.debug_poison) {
+        for (int32_t t = 0; t < L->T; ++t)
+            if ((st = check_extent(tensor_ptrs[t], static_cast<size_t>(L->numel[t]) * L->esz, fn, "a tensor")) != FCDP_OK) return st;
+        for (int32_t r = 0; r < L->G; ++r)
+            if ((r < first_shard || r >= first_shard + n_shards) &&
+                (st = check_extent(shard_ptrs[r], shard_bytes, fn, "a shard")) != FCDP_OK) return st;
+        if ((st = check_extent(staging_slice, slice_bytes, fn, "staging_slice")) != FCDP_OK) return st;
+        if ((st = poison_tensors(L, tensor_ptrs, compute)) != FCDP_OK) return st;
+    }
+    DeviceCtx::StagingUse *use = nullptr;
+    if ((st = staging_slot(ctx, staging_slice, &use)) != FCDP_OK) return st;
+    if (use->staging == staging_slice)
+        FCDP_HIP(hipStreamWaitEvent(copy, use->done, 0), "hipStreamWaitEvent(staging)");
+    if (tune.debug_poison) {
+        hipError_t pe = static_cast<hipError_t>(fcdp::launch_fill(staging_slice, slice_bytes, fcdp::kPoison, copy));
+        if (pe != hipSuccess) return hip_fail(pe, "launch poison fill (staging)");
+    }
+    if ((st = copy_admit(ctx)) != FCDP_OK) return st;
+    FCDP_HIP(hipMemcpyAsync(staging_slice, host_slice, slice_bytes, hipMemcpyHostToDevice, copy), "hipMemcpyAsync(H2D)");
+    if ((st = copy_enqueued(ctx, copy)) != FCDP_OK) return st;
+    if ((st = order_after(ctx, copy, compute)) != FCDP_OK) return st;
+    const void *small[FCDP_MAX_G];
+    for (int32_t r = 0; r < L->G; ++r)
+        small[r] = (r >= first_shard && r < first_shard + n_shards)
+                       ? static_cast<const char *>(staging_slice) + static_cast<size_t>(r - first_shard) * shard_bytes
+                       : shard_ptrs[r];
+    st = run_windowed(L->unflatten, tabs->unflatten, fcdp::TensorSide::Dst, L->T, small, L->G,
+                      reinterpret_cast<const void *const *>(tensor_ptrs), tune.copy_nt != 0,
+                      tune.copy_wg_per_cu, compute, "launch unflatten", FCDP_KERNEL_UNFLATTEN);
+    if (st != FCDP_OK) return st;
+    {
+        std::lock_guard<std::mutex> lk(ctx->mu);
+        FCDP_HIP(hipEventRecord(use->done, compute), "hipEventRecord(staging)");
+        use->staging = staging_slice;
+    }
+    ctx->fetched_bytes += static_cast<int64_t>(slice_bytes);
+    return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_materialize_layer_node_slice: out of host memory");
 }
 
 fcdp_status fcdp_link_bytes(int32_t reset, int64_t *stored, int64_t *fetched)

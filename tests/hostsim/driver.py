@@ -93,6 +93,22 @@ def check_layer(name, sizes, G, esz, offset):
         fcdp.fcdp_materialize_layer_static(L, H, outs, STREAM_A, STREAM_B)
         for t, w in enumerate(want):
             assert np.array_equal(outs[t].view(dt), w), (name, "static", t)
+    # one GPU's share of a node: every split of the G shards into equal parts that has
+    # more than one part, first and last part; exactly sized slice buffers
+    for g in [d for d in (2, 3, 4, 8) if G % d == 0 and S > 0]:
+        n = G // g
+        for first in sorted({0, G - n}):
+            Hs = fcdp.fcdp_host_cache_alloc(n * S * esz)
+            own = [d_shards[r] if first <= r < first + n else None for r in range(G)]
+            fcdp.fcdp_cache_store_node_slice(L, first, n, own, Hs, STREAM_A, STREAM_B)
+            assert np.array_equal(Hs.numpy(dt, n * S), flat[first * S:(first + n) * S]), (name, "slice store", g, first)
+            peers = [None if first <= r < first + n else d_shards[r] for r in range(G)]
+            outs = [Buf(k * esz, offset) for k in sizes]
+            stg = Buf(n * S * esz)
+            fcdp.fcdp_materialize_layer_node_slice(L, first, n, peers, Hs, stg, outs, STREAM_A, STREAM_B)
+            for t, w in enumerate(want):
+                assert np.array_equal(outs[t].view(dt), w), (name, "slice fetch", g, first, t)
+            Hs.free()
     H.free()
     L.destroy()
 

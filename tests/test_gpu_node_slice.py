@@ -1,0 +1,194 @@
+"""One GPU's share of a node (Sec. 4.3, backward pass: each GPU loads its 1/g
+part of the cached layer from host memory, the node's GPUs exchange the
+parts): the slice store and the slice fetch against the oracle.
+
+The oracle needs no new arithmetic: the slice store must leave the bytes of
+concat(own shards) in the host slice, and the fetch, given the host slice and
+the peers' shards on the device, must give what materialize_from_shards gives
+for all G shards."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2602_06499_amd as fcdp
+from paper_2602_06499_amd import synth
+from gpu_util import Arena
+
+pytestmark = pytest.mark.gpu
+
+
+def _rand_tensors(seed, sizes, dtype):
+    g = synth.rng(0, seed, synth.KIND_MISC, 23)
+    info = np.iinfo(dtype)
+    return [g.integers(0, int(info.max) + 1, size=k, dtype=dtype) for k in sizes]
+
+
+CASES = [  # G, GPUs per node g, element size, tensors, largest tensor
+    (4, 2, 2, 9, 70000), (8, 8, 2, 12, 300000), (8, 2, 4, 5, 50000), (16, 4, 2, 20, 90000),
+    (32, 8, 2, 7, 400000), (6, 3, 2, 4, 33333), (64, 8, 2, 30, 20000), (4, 4, 2, 3, 100),
+    (8, 1, 2, 6, 65536),      # g = 1: the slice is the whole layer
+]
+
+
+@pytest.mark.parametrize("G,g,esz,T,max_numel", CASES)
+def test_node_slice_store_and_fetch(G, g, esz, T, max_numel):
+    dt = np.uint16 if esz == 2 else np.uint32
+    sizes = synth.random_layer(7000 + G * 10 + g, T=T, max_numel=max_numel)
+    tensors = _rand_tensors(G * 100 + g, sizes, dt)
+    flat = oracle.flatten(tensors, G)
+    shards = oracle.split(flat, G)
+    want = oracle.materialize_from_shards(shards, sizes)
+    image = oracle.cache_store(shards)
+    L = fcdp.fcdp_layout_build(sizes, None, G, esz)
+    L.prepare()
+    S = L.shard_numel
+    n = G // g
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    sh = Arena([S * esz] * G)                       # G separate shard buffers
+    for r in range(G):
+        sh.fill(r, shards[r])
+    for k in range(g):                              # every GPU of the node in turn
+        first = k * n
+        H = fcdp.fcdp_host_cache_alloc(n * S * esz + 64)
+        H.numpy(np.uint8)[:] = 0x5A
+        # ---- store: only the slice's shard pointers are read
+        ptrs = [sh.ptr(r) if first <= r < first + n else None for r in range(G)]
+        fcdp.fcdp_link_bytes(True)
+        fcdp.fcdp_cache_store_node_slice(L, first, n, ptrs, H, compute, copy)
+        torch.cuda.synchronize()
+        assert np.array_equal(H.numpy(dt, n * S), image[first * S:(first + n) * S]), (k, "store")
+        assert np.all(H.numpy(np.uint8)[n * S * esz:] == 0x5A), "the store wrote past the slice"
+        assert fcdp.fcdp_link_bytes()[0] == n * S * esz
+        # ---- fetch: the slice from the host, every other shard from the device; the
+        # slice's own device pointers are not passed at all
+        peers = [None if first <= r < first + n else sh.ptr(r) for r in range(G)]
+        staging = Arena([n * S * esz])
+        out = Arena([kk * esz for kk in sizes])
+        fcdp.fcdp_link_bytes(True)
+        fcdp.fcdp_materialize_layer_node_slice(L, first, n, peers, H, staging.ptr(0), out.ptrs(), compute, copy)
+        torch.cuda.synchronize()
+        for t in range(len(sizes)):
+            assert np.array_equal(out.get(t, dt), want[t]), (k, "fetch", t)
+        out.check_guards()
+        staging.check_guards()
+        assert fcdp.fcdp_link_bytes()[1] == n * S * esz
+        H.free()
+    sh.check_guards()
+
+
+def test_node_slice_full_size_70b_share():
+    """One Llama-70B-shaped layer, G = 32, a node of 8 GPUs: GPU 3's share is
+    shards 12..15 (214 MB of the 1.7 GB layer); store, fetch, compare."""
+    cfg = synth.CONFIGS["llama70b_g32"]
+    G, g, k = cfg.G, 8, 3
+    n, first = G // g, 3 * (G // g)
+    dev = torch.device("cuda:0")
+    L = fcdp.fcdp_layout_build(cfg.numel, cfg.trainable, G, 2)
+    L.prepare()
+    Np, S = L.padded_numel, L.shard_numel
+    gen = synth.torch_device_generator(dev, cfg.config_id, 5, synth.KIND_PARAM)
+    gathered = torch.empty(Np, dtype=torch.bfloat16, device=dev).normal_(0.0, 0.02, generator=gen)
+    off = L.offsets
+    H = fcdp.fcdp_host_cache_alloc(n * S * 2)
+    staging = torch.empty(n * S, dtype=torch.bfloat16, device=dev)
+    tensors = [torch.zeros(max(kk, 1), dtype=torch.bfloat16, device=dev) for kk in cfg.numel]
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    all_ptrs = [gathered.data_ptr() + r * S * 2 for r in range(G)]
+    torch.cuda.synchronize()
+    fcdp.fcdp_cache_store_node_slice(L, first, n, all_ptrs, H, compute, copy)
+    torch.cuda.synchronize()
+    hs = torch.from_numpy(H.numpy(np.int16, n * S))
+    assert torch.equal(hs, gathered[first * S:(first + n) * S].cpu().view(torch.int16))
+    # the peers' shards on the device, this GPU's own range overwritten so that only the host copy can be right
+    scratch = gathered.clone()
+    scratch[first * S:(first + n) * S] = 0
+    peers = [None if first <= r < first + n else scratch.data_ptr() + r * S * 2 for r in range(G)]
+    torch.cuda.synchronize()
+    fcdp.fcdp_materialize_layer_node_slice(L, first, n, peers, H, staging, tensors, compute, copy)
+    torch.cuda.synchronize()
+    for t, kk in enumerate(cfg.numel):
+        assert torch.equal(tensors[t][:kk], gathered[off[t]:off[t] + kk]), t
+    # and against the oracle's definition on all G shards
+    flat = gathered.cpu().view(torch.int16).numpy().view(np.uint16)
+    want = oracle.materialize_from_shards([flat[r * S:(r + 1) * S] for r in range(G)], list(cfg.numel))
+    for t, kk in enumerate(cfg.numel):
+        assert np.array_equal(tensors[t][:kk].cpu().view(torch.int16).numpy().view(np.uint16), want[t]), t
+    H.free()
+
+
+def test_node_slice_arguments():
+    sizes, G = [4096, 100, 7000], 4
+    L = fcdp.fcdp_layout_build(sizes, None, G, 2)
+    L.prepare()
+    S = L.shard_numel
+    sh = Arena([S * 2] * G)
+    out = Arena([k * 2 for k in sizes])
+    staging = Arena([2 * S * 2])
+    H = fcdp.fcdp_host_cache_alloc(2 * S * 2)
+    for first, n in ((-1, 2), (3, 2), (0, 0), (0, 5), (4, 1)):
+        for call in (lambda: fcdp.fcdp_cache_store_node_slice(L, first, n, sh.ptrs(), H),
+                     lambda: fcdp.fcdp_materialize_layer_node_slice(L, first, n, sh.ptrs(), H, staging.ptr(0), out.ptrs())):
+            with pytest.raises(fcdp.FcdpError) as e:
+                call()
+            assert e.value.name == "FCDP_EINVAL", (first, n)
+    peers = sh.ptrs()
+    peers[0] = None                                 # a peer's shard is missing
+    with pytest.raises(fcdp.FcdpError) as e:
+        fcdp.fcdp_materialize_layer_node_slice(L, 1, 2, peers, H, staging.ptr(0), out.ptrs())
+    assert e.value.name == "FCDP_EINVAL"
+    with pytest.raises(fcdp.FcdpError) as e:
+        fcdp.fcdp_materialize_layer_node_slice(L, 1, 2, sh.ptrs(), H, None, out.ptrs())
+    assert e.value.name == "FCDP_EINVAL"
+    with pytest.raises(fcdp.FcdpError) as e:
+        fcdp.fcdp_materialize_layer_node_slice(L, 1, 2, sh.ptrs(), H.host + 2, staging.ptr(0), out.ptrs())
+    assert e.value.name == "FCDP_EALIGN"
+    own = [None, sh.ptr(1), sh.ptr(2), None]         # the store reads the slice's pointers only
+    fcdp.fcdp_cache_store_node_slice(L, 1, 2, own, H)
+    own[2] = None
+    with pytest.raises(fcdp.FcdpError) as e:
+        fcdp.fcdp_cache_store_node_slice(L, 1, 2, own, H)
+    assert e.value.name == "FCDP_EINVAL"
+    torch.cuda.synchronize()
+    out.check_guards()
+    H.free()
+
+
+def test_node_slice_backward_sweep_two_staging_slices():
+    """Eight layers fetched back to back through two alternating staging
+    slices with the copy stream held back at the start: every layer's tensors
+    are its own (the staging bookkeeping orders copy(l+2) after scatter(l))."""
+    sizes, G, g = [300000, 7, 65536, 123457], 8, 4
+    n, first = G // g, 2
+    L = fcdp.fcdp_layout_build(sizes, None, G, 2)
+    L.prepare()
+    S = L.shard_numel
+    nl = 8
+    layers = [_rand_tensors(600 + l, sizes, np.uint16) for l in range(nl)]
+    shards = [oracle.split(oracle.flatten(layers[l], G), G) for l in range(nl)]
+    H = fcdp.fcdp_host_cache_alloc(nl * n * S * 2)
+    for l in range(nl):
+        H.numpy(np.uint16, n * S, l * n * S * 2)[:] = np.concatenate(shards[l][first:first + n])
+    dev_sh = [Arena([S * 2] * G) for _ in range(nl)]
+    for l in range(nl):
+        for r in range(G):
+            if not first <= r < first + n:
+                dev_sh[l].fill(r, shards[l][r])
+    outs = [Arena([k * 2 for k in sizes]) for _ in range(nl)]
+    stg = Arena([n * S * 2, n * S * 2])
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(copy):
+        torch.cuda._sleep(50_000_000)
+    for l in range(nl - 1, -1, -1):
+        peers = [None if first <= r < first + n else dev_sh[l].ptr(r) for r in range(G)]
+        fcdp.fcdp_materialize_layer_node_slice(L, first, n, peers, H.host + l * n * S * 2, stg.ptr(l % 2),
+                                               outs[l].ptrs(), compute, copy)
+    torch.cuda.synchronize()
+    for l in range(nl):
+        want = oracle.materialize_from_shards(shards[l], sizes)
+        for t in range(len(sizes)):
+            assert np.array_equal(outs[l].get(t, np.uint16), want[t]), (l, t)
+        outs[l].check_guards()
+    stg.check_guards()
+    H.free()

@@ -676,6 +676,9 @@ def test_every_host_link_path_rejects_pageable_memory():
                                                                 out.ptrs(), fcdp.STORE_ZEROCOPY),
         "cache_store_dma": lambda h: fcdp.fcdp_cache_store(L, sh.ptrs(), h, fcdp.STORE_DMA),
         "cache_store_zerocopy": lambda h: fcdp.fcdp_cache_store(L, sh.ptrs(), h, fcdp.STORE_ZEROCOPY),
+        "node_slice_store": lambda h: fcdp.fcdp_cache_store_node_slice(L, 1, 2, sh.ptrs(), h),
+        "node_slice_fetch": lambda h: fcdp.fcdp_materialize_layer_node_slice(L, 1, 2, sh.ptrs(), h, staging.ptr(0),
+                                                                             out.ptrs()),
     }
     for name, call in calls.items():
         with pytest.raises(fcdp.FcdpError) as e:
