@@ -192,3 +192,60 @@ def test_node_slice_backward_sweep_two_staging_slices():
         outs[l].check_guards()
     stg.check_guards()
     H.free()
+
+
+def test_node_slice_training_loop_stays_coherent():
+    """Full fine-tuning over three iterations as GPU 1 of a node of 2 (Alg. 1's
+    flags decide: every forward is a miss, because the step dirtied the layer,
+    and refreshes this GPU's host slice; every backward is a hit and takes the
+    slice from the host and the other half from the peer's shards): the
+    tensors of both passes are the current parameters, never last step's."""
+    sizes, G, g, k = [50000, 3, 131072, 70001], 8, 2, 1
+    n, first = G // g, k * (G // g)
+    nl, iters = 3, 3
+    L = fcdp.fcdp_layout_build(sizes, None, G, 2)
+    L.prepare()
+    S = L.shard_numel
+    rng = synth.rng(0, 808, synth.KIND_MISC)
+    params = [[rng.integers(0, 65536, size=kk, dtype=np.uint16) for kk in sizes] for _ in range(nl)]
+    H = fcdp.fcdp_host_cache_alloc(nl * n * S * 2)
+    H.numpy(np.uint16)[:] = 0xDEAD
+    state = fcdp.CacheState(nl)
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    stg = Arena([n * S * 2, n * S * 2])
+    for it in range(iters):
+        gathered = []
+        for l in range(nl):                                   # ---- forward
+            src, store = state.forward_source(l, 1, fcdp.SRC_HOST_DMA)
+            assert (src, store) == (fcdp.SRC_DEVICE_SHARDS, True)
+            shards = oracle.split(oracle.flatten(params[l], G), G)
+            sh = Arena([S * 2] * G)                           # what the inter-node gather delivered
+            for r in range(G):
+                sh.fill(r, shards[r])
+            gathered.append((sh, shards))
+            out = Arena([kk * 2 for kk in sizes])
+            fcdp.fcdp_materialize_layer(L, src, sh.ptrs(), None, None, out.ptrs(), fcdp.STORE_NONE, compute, copy)
+            fcdp.fcdp_cache_store_node_slice(L, first, n, sh.ptrs(), H.host + l * n * S * 2, compute, copy)
+            torch.cuda.synchronize()
+            for t in range(len(sizes)):
+                assert np.array_equal(out.get(t, np.uint16), params[l][t]), ("forward", it, l, t)
+        for l in range(nl - 1, -1, -1):                       # ---- backward
+            assert state.backward_source(l, 1, fcdp.SRC_HOST_DMA) == fcdp.SRC_HOST_DMA
+            sh, shards = gathered[l]
+            # after the forward pass only the peer's half is back on this GPU (the exchange inside
+            # the node); this GPU's own half of the gathered buffer was freed: overwrite it
+            for r in range(first, first + n):
+                sh.fill(r, np.full(S, 0xBEEF, dtype=np.uint16))
+            peers = [None if first <= r < first + n else sh.ptr(r) for r in range(G)]
+            out = Arena([kk * 2 for kk in sizes])
+            fcdp.fcdp_materialize_layer_node_slice(L, first, n, peers, H.host + l * n * S * 2, stg.ptr(l % 2),
+                                                   out.ptrs(), compute, copy)
+            torch.cuda.synchronize()
+            for t in range(len(sizes)):
+                assert np.array_equal(out.get(t, np.uint16), params[l][t]), ("backward", it, l, t)
+            out.check_guards()
+        for l in range(nl):                                   # ---- the optimizer changes every parameter
+            params[l] = [(p + np.uint16(it * 7 + l + 1)).astype(np.uint16) for p in params[l]]
+        state.optimizer_step()
+    stg.check_guards()
+    H.free()
