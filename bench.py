@@ -84,8 +84,9 @@ def parse():
     ap.add_argument("--no-peft-leg", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--cpu-sample-layers", type=int, default=3)
-    ap.add_argument("--cpu-threads", type=int, default=4,
-                    help="threads of the all-threads oracle leg (one layer each)")
+    ap.add_argument("--cpu-threads", type=int, default=16,
+                    help="threads of the all-threads oracle leg (one layer each; capped at the host's cores; "
+                         "about 5 GB of host memory per thread at the 70B shape)")
     ap.add_argument("--probe-gib", type=int, default=16,
                     help="size of the host-link probe copy (16: the transfer size of the paper's Table 3, first row)")
     ap.add_argument("--reduce-study", action="store_true",
@@ -561,7 +562,7 @@ def main():
     if not args.no_cpu_baseline:
         # host copies of a few layers for the oracle, taken before the device buffers go
         n_s = max(1, min(args.cpu_sample_layers, stack.K, stack.Kg))
-        n_t = max(1, min(args.cpu_threads, stack.K, stack.Kg, os.cpu_count() or 1))
+        n_t = max(1, min(args.cpu_threads, stack.K, stack.Kg, os.cpu_count() or 1))   # distinct input layers
         cpu_inputs = []
         for l in range(max(n_s, n_t)):
             flat = stack.gathered[l].cpu().view(torch.int16).numpy().view(np.uint16)
@@ -798,7 +799,10 @@ def main():
         # the same oracle, one layer per thread (ctypes releases the GIL): what the
         # host's cores give together, still nothing tuned
         from concurrent.futures import ThreadPoolExecutor
-        n_t = max(1, min(args.cpu_threads, len(cpu_inputs)))
+        # every thread its own layer's worth of work; threads beyond the distinct input layers
+        # read one of them again (inputs are only read, every thread writes its own outputs)
+        n_t = max(1, min(args.cpu_threads, os.cpu_count() or 1))
+        work = [cpu_inputs[i % len(cpu_inputs)] for i in range(n_t)]
 
         def one_layer(w):
             shards, parts = w
@@ -809,9 +813,9 @@ def main():
 
         with ThreadPoolExecutor(n_t) as pool:
             t0 = time.perf_counter()
-            list(pool.map(one_layer, cpu_inputs[:n_t]))
+            list(pool.map(one_layer, work))
             t_par = time.perf_counter() - t0
-        cpu_inputs = None
+        cpu_inputs = work = None
         if peft is not None:
             # the PEFT steps of one LoRA layer on the same oracle (one thread)
             pflat_h = pflat.cpu().view(torch.int16).numpy().view(np.uint16)
