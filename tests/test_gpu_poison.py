@@ -14,6 +14,7 @@ from gpu_util import Arena
 
 import test_gpu_alg1_loop as loop
 import test_gpu_stream_order as order
+import test_gpu_node_slice as node
 
 pytestmark = pytest.mark.gpu
 
@@ -43,6 +44,15 @@ def test_stream_order_under_poison(poison):
     order.test_store_waits_for_a_late_producer(fcdp.STORE_DMA)
     order.test_staging_reuse_waits_for_a_late_scatter()
     order.test_scatter_dma_waits_for_earlier_readers()
+
+
+def test_node_slice_under_poison(poison):
+    """The slice store and fetch with the fills and the extent checks on: same
+    bytes, and the arenas' guards (checked inside) stay untouched."""
+    node.test_node_slice_store_and_fetch(8, 2, 4, 5, 50000)
+    node.test_node_slice_store_and_fetch(16, 4, 2, 20, 90000)
+    node.test_node_slice_backward_sweep_two_staging_slices()
+    node.test_node_slice_training_loop_stays_coherent()
 
 
 def test_poison_is_written_first(poison):
