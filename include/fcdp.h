@@ -381,6 +381,21 @@ fcdp_status fcdp_pack_trainable(const fcdp_layout *layout, const void *flat,
 fcdp_status fcdp_unpack_trainable(const fcdp_layout *layout,
                                   const void *packed, void *flat,
                                   fcdp_stream stream);
+/* Unpack for a GPU that holds only its node slice of the flat image (the
+ * shards [first_shard, first_shard + n_shards), see
+ * fcdp_materialize_layer_node_slice): writes the trainable elements that
+ * fall into those shards and nothing else.
+ *   packed      dev ptr, packed_numel elements (the whole packed buffer)
+ *   flat_slice  dev ptr, n_shards*S elements: the slice, e.g. the device
+ *               alias of this GPU's part of the mapped host cache (Alg. 1's
+ *               refresh of H for W_t, on this GPU's share)
+ * Errors as for fcdp_unpack_trainable, FCDP_EINVAL for a slice outside [0, G). */
+fcdp_status fcdp_unpack_trainable_node_slice(const fcdp_layout *layout,
+                                             int32_t first_shard,
+                                             int32_t n_shards,
+                                             const void *packed,
+                                             void *flat_slice,
+                                             fcdp_stream stream);
 
 /* ------------------------------------------------------------- host cache
  * Pinned, device-mapped host memory for the cache H (Sec. 4.4, host memory:

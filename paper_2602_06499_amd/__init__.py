@@ -11,7 +11,7 @@ from .binding import (  # noqa: F401
     FcdpError, Layout, CacheState, HostCache,
     fcdp_layout_build, fcdp_materialize_layer, fcdp_flatten_to_shards,
     fcdp_materialize_layer_static, STATIC_STAGING_BYTES,
-    fcdp_cache_store_node_slice, fcdp_materialize_layer_node_slice,
+    fcdp_cache_store_node_slice, fcdp_materialize_layer_node_slice, fcdp_unpack_trainable_node_slice,
     fcdp_reduce_grad_shard, fcdp_reduce_trainable_shard, fcdp_pack_trainable, fcdp_unpack_trainable,
     fcdp_reduce_grad_shard_scaled, fcdp_reduce_trainable_shard_scaled,
     fcdp_host_cache_alloc, fcdp_host_cache_free, fcdp_tuning_set,

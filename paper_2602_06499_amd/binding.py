@@ -46,7 +46,7 @@ EXPORTS = [
     "fcdp_cache_store_node_slice", "fcdp_materialize_layer_node_slice",
     "fcdp_reduce_grad_shard", "fcdp_reduce_trainable_shard",
     "fcdp_reduce_grad_shard_scaled", "fcdp_reduce_trainable_shard_scaled",
-    "fcdp_pack_trainable", "fcdp_unpack_trainable",
+    "fcdp_pack_trainable", "fcdp_unpack_trainable", "fcdp_unpack_trainable_node_slice",
     "fcdp_host_cache_alloc", "fcdp_host_cache_free",
     "fcdp_cache_state_create", "fcdp_cache_state_destroy",
     "fcdp_cache_state_forward_source", "fcdp_cache_state_backward_source",
@@ -107,6 +107,7 @@ def load_library() -> ctypes.CDLL:
     lib.fcdp_flatten_to_shards.argtypes = [vp, vp, vp, vp]
     lib.fcdp_cache_store.argtypes = [vp, vp, vp, c.c_int, vp, vp]
     lib.fcdp_cache_store_node_slice.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+    lib.fcdp_unpack_trainable_node_slice.argtypes = [vp, i32, i32, vp, vp, vp]
     lib.fcdp_materialize_layer_node_slice.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.fcdp_cache_state_set_tau.argtypes = [vp, c.c_double]
     lib.fcdp_cache_state_place.argtypes = [vp, i32, i64, i64, c.POINTER(i32)]
@@ -343,6 +344,12 @@ def fcdp_pack_trainable(layout: Layout, flat, packed, stream=None) -> None:
 def fcdp_unpack_trainable(layout: Layout, packed, flat, stream=None) -> None:
     _check(load_library().fcdp_unpack_trainable(
         layout.handle, _ptr(packed), _ptr(flat), _stream(stream)))
+
+
+def fcdp_unpack_trainable_node_slice(layout: Layout, first_shard: int, n_shards: int, packed,
+                                     flat_slice, stream=None) -> None:
+    _check(load_library().fcdp_unpack_trainable_node_slice(
+        layout.handle, first_shard, n_shards, _ptr(packed), _ptr(flat_slice), _stream(stream)))
 
 
 class HostCache:

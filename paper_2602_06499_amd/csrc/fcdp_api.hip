@@ -1041,6 +1041,56 @@ try {
     return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_unpack_trainable: out of host memory");
 }
 
+fcdp_status fcdp_unpack_trainable_node_slice(const fcdp_layout *L, int32_t first_shard, int32_t n_shards,
+                                             const void *packed, void *flat_slice, fcdp_stream stream)
+try {
+    const char *fn = "fcdp_unpack_trainable_node_slice";
+    if (!L) return fail(FCDP_EINVAL, std::string(fn) + ": layout is NULL");
+    fcdp_status st = check_node_slice(L, first_shard, n_shards, fn);
+    if (st != FCDP_OK) return st;
+    if (!packed || !flat_slice) return fail(FCDP_EINVAL, std::string(fn) + ": NULL buffer");
+    if (!aligned16(packed) || !aligned16(flat_slice))
+        return fail(FCDP_EALIGN, std::string(fn) + ": buffer not 16-byte aligned");
+    const int64_t shard_bytes = L->S * L->esz;
+    const int64_t lo = first_shard * shard_bytes, hi = lo + n_shards * shard_bytes; // the slice's flat byte range
+    const int64_t pb = L->N_packed * L->esz;
+    const char *sl = static_cast<const char *>(flat_slice), *pk = static_cast<const char *>(packed);
+    if (hi > lo && pb > 0 && sl < pk + pb && pk < sl + (hi - lo))
+        return fail(FCDP_EINVAL, std::string(fn) + ": flat_slice and packed overlap");
+    // the table is in ascending destination order and cut at shard boundaries: the pieces
+    // that write into [lo, hi) are one contiguous part of it
+    const std::vector<fcdp::Piece> &pcs = L->unpack.pieces;
+    const auto first = std::lower_bound(pcs.begin(), pcs.end(), lo,
+                                        [](const fcdp::Piece &p, int64_t v) { return p.dst_off < v; });
+    const auto last = std::lower_bound(first, pcs.end(), hi,
+                                       [](const fcdp::Piece &p, int64_t v) { return p.dst_off < v; });
+    if (first == last) return FCDP_OK;               // no trainable element lives in this slice
+    if (fcdp::tuning().debug_poison) {
+        if ((st = check_extent(flat_slice, static_cast<size_t>(hi - lo), fn, "flat_slice")) != FCDP_OK) return st;
+        if ((st = check_extent(packed, static_cast<size_t>(pb), fn, "packed")) != FCDP_OK) return st;
+    }
+    const fcdp::DeviceTables *tabs = nullptr;
+    if ((st = tables_for_current_device(L, &tabs)) != FCDP_OK) return st;
+    // the pieces carry offsets into the whole flat buffer: hand the kernel the address the
+    // whole buffer would start at; only [lo, hi) of it is touched
+    const void *small[2] = {packed, reinterpret_cast<void *>(reinterpret_cast<uintptr_t>(flat_slice) -
+                                                            static_cast<uintptr_t>(lo))};
+    fcdp::CopyLaunch c;
+    c.pieces = tabs->unpack + (first - pcs.begin());
+    c.n_pieces = static_cast<int64_t>(last - first);
+    c.tensor_side = fcdp::TensorSide::None;
+    c.small_ptrs = small;
+    c.n_small = 2;
+    c.nt = false;
+    c.wg_per_cu = 0;
+    c.ev = timing_events(FCDP_KERNEL_UNPACK);
+    hipError_t e = static_cast<hipError_t>(fcdp::launch_copy(c, stream));
+    if (e != hipSuccess) return hip_fail(e, fn);
+    return FCDP_OK;
+} catch (...) {
+    return fcdp::fail_noexcept(FCDP_ENOMEM, "fcdp_unpack_trainable_node_slice: out of host memory");
+}
+
 // ------------------------------------------------------------- host cache
 
 fcdp_status fcdp_host_cache_alloc(size_t bytes, int numa_node, void **host, void **dev_alias)

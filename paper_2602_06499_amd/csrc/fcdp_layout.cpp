@@ -159,7 +159,15 @@ fcdp_status build_tables(fcdp_layout *L)
             ++u;
         }
         emit_run(L->pack.pieces, 0, L->off[t] * e, 0, c * e, run * e, chunk);
-        emit_run(L->unpack.pieces, 0, c * e, 0, L->off[t] * e, run * e, chunk);
+        // unpack pieces are also cut at the shard boundaries of the flat buffer, so that the
+        // pieces that write one range of shards are a contiguous part of the table (a GPU that
+        // holds only its node slice of the flat image unpacks exactly those)
+        for (int64_t lo = L->off[t], done = 0; done < run;) {
+            const int64_t hi = std::min(L->off[t] + run, S > 0 ? (lo / S + 1) * S : L->off[t] + run);
+            emit_run(L->unpack.pieces, 0, (c + done) * e, 0, lo * e, (hi - lo) * e, chunk);
+            done += hi - lo;
+            lo = hi;
+        }
         c += run;
         t = u;
     }

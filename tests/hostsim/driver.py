@@ -154,6 +154,14 @@ def check_peft(name, sizes, tr, G, esz):
     d_new = dev(newp) if Pn else Buf(16)
     fcdp.fcdp_unpack_trainable(L, d_new, d_flat, None)
     assert np.array_equal(d_flat.view(dt), ref), (name, "unpack")
+    # the same unpack clipped to a node slice, into exactly sized slice buffers
+    S = L.shard_numel
+    for gg in [d for d in (2, 4) if G % d == 0 and S > 0]:
+        n = G // gg
+        for first in range(0, G, n):
+            d_slice = dev(flat[first * S:(first + n) * S])
+            fcdp.fcdp_unpack_trainable_node_slice(L, first, n, d_new, d_slice, None)
+            assert np.array_equal(d_slice.view(dt), ref[first * S:(first + n) * S]), (name, "slice unpack", gg, first)
     if esz != 2 or Pn == 0:
         return
     # fused pack + reduce from G flat fp32 / bf16 gradients

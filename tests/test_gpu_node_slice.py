@@ -249,3 +249,131 @@ def test_node_slice_training_loop_stays_coherent():
         state.optimizer_step()
     stg.check_guards()
     H.free()
+
+
+UNPACK_CASES = [  # G, g, element size, tensors, largest tensor
+    (4, 2, 2, 9, 70000), (8, 4, 2, 14, 30000), (8, 8, 4, 6, 50000), (16, 2, 2, 25, 9000),
+    (6, 3, 2, 5, 33333), (32, 8, 2, 40, 20000), (4, 4, 2, 3, 50),
+]
+
+
+@pytest.mark.parametrize("G,g,esz,T,max_numel", UNPACK_CASES)
+def test_unpack_into_a_node_slice(G, g, esz, T, max_numel):
+    """Unpack restricted to a GPU's shards: the slice ends up as the same
+    range of the flat image the oracle's unpack produces; frozen bytes of the
+    slice and everything around it stay as they were."""
+    dt = np.uint16 if esz == 2 else np.uint32
+    sizes = synth.random_layer(8100 + G * 10 + g, T=T, max_numel=max_numel)
+    rng = synth.rng(0, 8200 + G + g, synth.KIND_MISC)
+    tr = [int(v) for v in rng.integers(0, 2, size=T)]
+    if g == 4 and G == 4:
+        tr = [0] * T                                # no trainable tensor at all: a no-op
+    tensors = _rand_tensors(G * 100 + g + 7, sizes, dt)
+    flat = oracle.flatten(tensors, G)
+    L = fcdp.fcdp_layout_build(sizes, tr, G, esz)
+    L.prepare()
+    S, Pn = L.shard_numel, L.packed_numel
+    info = np.iinfo(dt)
+    packed = rng.integers(0, int(info.max) + 1, size=Pn, dtype=dt)
+    want_flat = flat.copy()
+    oracle.unpack(packed, want_flat, sizes, tr)
+    d_packed = Arena([max(Pn * esz, 16)])
+    if Pn:
+        d_packed.fill(0, packed)
+    n = G // g
+    st = torch.cuda.Stream()
+    for k in range(g):
+        first = k * n
+        sl = Arena([max(n * S * esz, 16)])
+        if n * S:
+            sl.fill(0, flat[first * S:(first + n) * S])   # the slice before the refresh
+        torch.cuda.synchronize()
+        fcdp.fcdp_unpack_trainable_node_slice(L, first, n, d_packed.ptr(0), sl.ptr(0), st)
+        torch.cuda.synchronize()
+        if n * S:
+            assert np.array_equal(sl.get(0, dt), want_flat[first * S:(first + n) * S]), (k, "slice")
+        sl.check_guards()
+    d_packed.check_guards()
+    if any(tr) and L.trainable_numel:
+        # the slices together changed exactly what the whole-buffer unpack changes
+        assert not np.array_equal(want_flat, flat) or np.array_equal(packed[:L.trainable_numel],
+                                                                    oracle.pack(flat, sizes, tr, G)[:L.trainable_numel])
+
+
+def test_peft_loop_through_node_slices():
+    """Alg. 1 under PEFT as GPU 0 of a node of 2, three iterations: the first
+    forward is a miss (store this GPU's slice); later forwards hit for the
+    frozen class and refresh the trainable ranges of this GPU's host slice by
+    the clipped unpack through the mapping; every backward takes the slice
+    from the host.  The tensors are always the current parameters."""
+    sizes, G, g, k = [40000, 4096, 77777, 512, 90001], 4, 2, 0
+    trainable = [0, 1, 0, 1, 0]
+    n, first = G // g, k * (G // g)
+    nl, iters = 2, 3
+    L = fcdp.fcdp_layout_build(sizes, trainable, G, 2)
+    L.prepare()
+    S = L.shard_numel
+    rng = synth.rng(0, 909, synth.KIND_MISC)
+    params = [[rng.integers(0, 65536, size=kk, dtype=np.uint16) for kk in sizes] for _ in range(nl)]
+    caches = [fcdp.fcdp_host_cache_alloc(n * S * 2) for _ in range(nl)]
+    for H in caches:
+        H.numpy(np.uint16)[:] = 0xDEAD
+    state = fcdp.CacheState(nl)
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    stg = Arena([n * S * 2, n * S * 2])
+    kinds = []
+    for it in range(iters):
+        for l in range(nl):                                   # ---- forward
+            flat = oracle.flatten(params[l], G)
+            shards = oracle.split(flat, G)
+            dec = {c: state.forward_source(l, c, fcdp.SRC_HOST_DMA) for c in (0, 1)}
+            sh = Arena([S * 2] * G)
+            out = Arena([kk * 2 for kk in sizes])
+            if all(src == fcdp.SRC_DEVICE_SHARDS for src, _ in dec.values()):
+                for r in range(G):
+                    sh.fill(r, shards[r])                     # everything was gathered
+                fcdp.fcdp_materialize_layer(L, fcdp.SRC_DEVICE_SHARDS, sh.ptrs(), None, None, out.ptrs(),
+                                            fcdp.STORE_NONE, compute, copy)
+                fcdp.fcdp_cache_store_node_slice(L, first, n, sh.ptrs(), caches[l], compute, copy)
+                kinds.append("miss")
+            else:
+                assert dec[0] == (fcdp.SRC_HOST_DMA, False) and dec[1] == (fcdp.SRC_DEVICE_SHARDS, True)
+                # only the packed trainable values crossed the node boundary: refresh this GPU's
+                # slice of H with them, then fetch the slice; the peer's shards hold current values
+                d_packed = Arena([L.packed_numel * 2])
+                d_packed.fill(0, oracle.pack(flat, sizes, trainable, G))
+                for r in range(G):
+                    if not first <= r < first + n:
+                        sh.fill(r, shards[r])
+                fcdp.fcdp_unpack_trainable_node_slice(L, first, n, d_packed.ptr(0), caches[l].dev, copy)
+                peers = [None if first <= r < first + n else sh.ptr(r) for r in range(G)]
+                fcdp.fcdp_materialize_layer_node_slice(L, first, n, peers, caches[l], stg.ptr(l % 2), out.ptrs(),
+                                                       compute, copy)
+                kinds.append("refresh")
+            torch.cuda.synchronize()
+            for t in range(len(sizes)):
+                assert np.array_equal(out.get(t, np.uint16), params[l][t]), ("forward", it, l, t)
+            assert np.array_equal(caches[l].numpy(np.uint16, n * S), flat[first * S:(first + n) * S]), "host slice is stale"
+        for l in range(nl - 1, -1, -1):                       # ---- backward: hits for both classes
+            for c in (0, 1):
+                assert state.backward_source(l, c, fcdp.SRC_HOST_DMA) == fcdp.SRC_HOST_DMA
+            shards = oracle.split(oracle.flatten(params[l], G), G)
+            sh = Arena([S * 2] * G)
+            for r in range(G):
+                if not first <= r < first + n:
+                    sh.fill(r, shards[r])
+            peers = [None if first <= r < first + n else sh.ptr(r) for r in range(G)]
+            out = Arena([kk * 2 for kk in sizes])
+            fcdp.fcdp_materialize_layer_node_slice(L, first, n, peers, caches[l], stg.ptr(l % 2), out.ptrs(),
+                                                   compute, copy)
+            torch.cuda.synchronize()
+            for t in range(len(sizes)):
+                assert np.array_equal(out.get(t, np.uint16), params[l][t]), ("backward", it, l, t)
+        for l in range(nl):                                   # ---- the step changes the trainable tensors only
+            for t in range(len(sizes)):
+                if trainable[t]:
+                    params[l][t] = (params[l][t] + np.uint16(3 + it)).astype(np.uint16)
+        state.optimizer_step()
+    assert kinds == ["miss"] * nl + ["refresh"] * (nl * (iters - 1))
+    for H in caches:
+        H.free()
