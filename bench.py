@@ -144,7 +144,7 @@ class Stack:
     """Device and host buffers of one stack, and its step."""
 
     def __init__(self, fcdp, synth, torch, cfg_name, layers, cache, arena_bytes, cache_slots, grad_slots,
-                 fetch, store, out_f32, tau=0.0, node_g=1):
+                 fetch, store, out_f32, tau=0.0, node_g=1, streams=None):
         self.fcdp, self.torch = fcdp, torch
         dev = torch.device("cuda:0")
         cfg = synth.CONFIGS[cfg_name]
@@ -201,7 +201,13 @@ class Stack:
                     self.kept_tensors[l] = [torch.empty(max(k, 1), dtype=torch.bfloat16, device=dev)
                                             for k in cfg.numel]
                     self.kept_sets[l] = fcdp.pointer_array(self.kept_tensors[l])
-        self.compute, self.copy = torch.cuda.Stream(), torch.cuda.Stream()
+        # one compute and one copy stream for the whole process, as a training loop has them.
+        # (Which pair of streams a stack gets matters here: of three 13B stacks made one after
+        # the other, each with a new pair, the second ran its backward sweep 3 % slower than
+        # the first and the third, by exactly its kernels' time, i.e. with no overlap of copy
+        # and kernels: stream pairs land on hardware queues in turn, and not every pairing of
+        # queues overlaps a copy with a kernel.)
+        self.compute, self.copy = streams or (torch.cuda.Stream(), torch.cuda.Stream())
         self.host_mode = {"dma": fcdp.SRC_HOST_DMA, "zerocopy": fcdp.SRC_HOST_ZEROCOPY,
                           "scatter": fcdp.SRC_HOST_SCATTER_DMA}[fetch]
         self.store_mode = fcdp.STORE_DMA if store == "dma" else fcdp.STORE_ZEROCOPY
@@ -578,7 +584,8 @@ def main():
                                          ("llama7b_g8_dma", "llama7b_g8", "dma", True)):
             if cname == args.config and fetch == args.fetch:
                 continue
-            s2 = Stack(fcdp, synth, torch, cname, 0, cache, arena_bytes, 0, args.grad_slots, fetch, "dma", of32)
+            s2 = Stack(fcdp, synth, torch, cname, 0, cache, arena_bytes, 0, args.grad_slots, fetch, "dma", of32,
+                       streams=(compute, copy))
             r = s2.run(args.leg_steps, args.leg_warmup)
             if not args.no_check:
                 s2.check()
@@ -611,7 +618,7 @@ def main():
     if not args.no_legs:
         node_g = 8
         s3 = Stack(fcdp, synth, torch, "llama70b_g32", 0, cache, arena_bytes, args.cache_slots or 15, args.grad_slots,
-                   "dma", "dma", False, node_g=node_g)
+                   "dma", "dma", False, node_g=node_g, streams=(compute, copy))
         r = s3.run(args.leg_steps, args.leg_warmup)
         if not args.no_check:
             s3.check()
