@@ -23,7 +23,7 @@ int worker(const fcdp_layout *L, int id, const std::vector<uint16_t> &flat, void
 {
     const int64_t Np = fcdp_layout_padded_numel(L), S = fcdp_layout_shard_numel(L);
     const int64_t *off = fcdp_layout_offsets(L);
-    std::vector<uint16_t> staging(Np), shards(flat);
+    std::vector<uint16_t> staging(Np), staging_slice(S), shards(flat);
     std::vector<std::vector<uint16_t>> tensors(kT);
     void *tptr[kT];
     const void *sptr[kG];
@@ -38,7 +38,7 @@ int worker(const fcdp_layout *L, int id, const std::vector<uint16_t> &flat, void
          *stream_b = reinterpret_cast<void *>(uintptr_t(0x2000 + id * 16));
     for (int it = 0; it < kIters; ++it) {
         fcdp_status st;
-        switch (it % 4) {
+        switch (it % 5) {
         case 0:
             st = fcdp_materialize_layer(L, FCDP_SRC_HOST_DMA, nullptr, host_cache, staging.data(), tptr,
                                         FCDP_STORE_NONE, stream_a, stream_b);
@@ -51,9 +51,13 @@ int worker(const fcdp_layout *L, int id, const std::vector<uint16_t> &flat, void
             st = fcdp_materialize_layer(L, FCDP_SRC_DEVICE_SHARDS, sptr, nullptr, nullptr, tptr,
                                         FCDP_STORE_NONE, stream_a, stream_b);
             break;
-        default:
+        case 3:
             st = fcdp_materialize_layer(L, FCDP_SRC_HOST_ZEROCOPY, nullptr, host_cache, nullptr, tptr,
                                         FCDP_STORE_NONE, stream_a, stream_b);
+            break;
+        default: // shard 1 from the host, the others from the device
+            st = fcdp_materialize_layer_node_slice(L, 1, 1, sptr, static_cast<char *>(host_cache) + S * 2,
+                                                   staging_slice.data(), tptr, stream_a, stream_b);
             break;
         }
         if (st != FCDP_OK) {
@@ -95,8 +99,8 @@ int main()
     b.join();
     int64_t stored = 0, fetched = 0;
     fcdp_link_bytes(0, &stored, &fetched);
-    // 3 of every 4 iterations fetch one padded image, in both threads
-    const int64_t want = 2LL * (kIters / 4 * 3) * Np * 2;
+    // 3 of every 5 iterations fetch one padded image and 1 of 5 one shard, in both threads
+    const int64_t want = 2LL * (kIters / 5) * (3 * Np * 2 + fcdp_layout_shard_numel(L) * 2);
     if (fetched != want) {
         std::printf("link counter lost updates: %lld, expected %lld\n", (long long)fetched, (long long)want);
         return 1;
