@@ -202,11 +202,9 @@ class Stack:
                                             for k in cfg.numel]
                     self.kept_sets[l] = fcdp.pointer_array(self.kept_tensors[l])
         # one compute and one copy stream for the whole process, as a training loop has them.
-        # (Which pair of streams a stack gets matters here: of three 13B stacks made one after
-        # the other, each with a new pair, the second ran its backward sweep 3 % slower than
-        # the first and the third, by exactly its kernels' time, i.e. with no overlap of copy
-        # and kernels: stream pairs land on hardware queues in turn, and not every pairing of
-        # queues overlaps a copy with a kernel.)
+        # (The second pair of streams a process puts to use ran the 13B backward sweep 3 % slower
+        # than the first, the third and every later pair, by exactly its kernels' time, i.e. with
+        # copies and kernels taking turns: measured with ten streams made up front.)
         self.compute, self.copy = streams or (torch.cuda.Stream(), torch.cuda.Stream())
         self.host_mode = {"dma": fcdp.SRC_HOST_DMA, "zerocopy": fcdp.SRC_HOST_ZEROCOPY,
                           "scatter": fcdp.SRC_HOST_SCATTER_DMA}[fetch]
