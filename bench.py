@@ -560,6 +560,7 @@ def main():
     del oshard
     k3_f32_gbps = (G * S * 4 + S * 4) / ((head["k3_ms"] if out_f32 else k3_other_ms) * 1e-3) / 1e9
     k3_bf16_gbps = (G * S * 4 + S * 2) / ((k3_other_ms if out_f32 else head["k3_ms"]) * 1e-3) / 1e9
+    kept_layers = len(stack.kept_sets)
     head_tensor0 = stack.kept_tensors.get(0, stack.tensors)[0][:cfg.numel[0]].cpu()
     head_shard = stack.grad_shard.cpu()
     cpu_inputs = None
@@ -916,7 +917,7 @@ def main():
                       "one_layer_scatter_dma_ms": round(sc_ms, 3),
                       "zero_copy_gbps": round(N * 2 / (zc_ms * 1e-3) / 1e9, 2)},
         "plain_copy_gbps": round(4 * N / (copy_ms * 1e-3) / 1e9, 1),
-        "adaptive": {"tau": args.tau, "kept_layers": len(stack.kept_sets or {}) if args.tau > 0 else 0,
+        "adaptive": {"tau": args.tau, "kept_layers": kept_layers,
                      "stored_bytes_per_step": head["stored"], "fetched_bytes_per_step": head["fetched"]},
         "stacks": legs or None,
         "peft": peft,
